@@ -1,0 +1,7 @@
+"""MI355X-native verification step of Speech Speculative Decoding: thin Python binding over libssd.so.
+
+Everything of the method runs in the HIP kernels behind the C ABI of include/ssd.h; this package only
+marshals arguments (torch tensors provide device memory and the stream)."""
+from .binding import (SSDError, Model, KVCache, SampleConfig, sample_config, load_library, library_path,  # noqa: F401
+                      upload_weights, ssd_verify, ssd_draft_step, ssd_kv_rollback, ssd_kv_follow,
+                      ssd_verify_from_probs, ssd_warp_probs, ssd_prefill, EXPORTED_SYMBOLS)

@@ -1,0 +1,163 @@
+// Device-side helpers shared by the kernels of libssd (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssd {
+
+constexpr int WAVE = 64;
+constexpr int BLOCK = 256;            // threads per workgroup of every kernel here (4 waves)
+constexpr int ATT_CHUNK = 64;         // keys per attention work item; chunk c covers positions [64c, 64c+64)
+
+typedef uint16_t bf16_t;              // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ float bf16_to_f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f_to_bf16(float f) {   // round to nearest even (finite inputs)
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// Storage types of activations / weights / KV: load as float, store from float.
+struct F32 {
+  typedef float T;
+  static __device__ __forceinline__ float ld(const T* p) { return *p; }
+  static __device__ __forceinline__ void st(T* p, float v) { *p = v; }
+};
+struct BF16 {
+  typedef bf16_t T;
+  static __device__ __forceinline__ float ld(const T* p) { return bf16_to_f(*p); }
+  static __device__ __forceinline__ void st(T* p, float v) { *p = f_to_bf16(v); }
+};
+
+// Butterfly reductions over the 64 lanes of a wave: every lane ends with the same value, and the
+// association order is fixed, so results do not depend on anything but the inputs.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+
+// Block-wide (256 threads) reductions through a 4-entry LDS array; all threads get the result.
+__device__ __forceinline__ float block_sum(float v, float* s4) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (s4[0] + s4[1]) + (s4[2] + s4[3]);
+}
+__device__ __forceinline__ float block_max(float v, float* s4) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
+}
+
+// Philox-4x32-10 (Salmon et al., SC'11).  Counter (slot, seq, step_lo, step_hi), key (seed_lo, seed_hi).
+// Returns output word 0; the uniform of a slot is its top 24 bits times 2^-24.
+__device__ __forceinline__ uint32_t philox_word0(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return c0;
+}
+__device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t seq, uint64_t step, uint32_t slot) {
+  const uint32_t w = philox_word0(slot, seq, (uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seed,
+                                  (uint32_t)(seed >> 32));
+  return (float)(w >> 8) * 5.9604644775390625e-08f;   // exact: 24-bit integer times 2^-24
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Device-resident state of a paged KV cache (all pointers into caller-provided device memory).
+struct KvView {
+  int32_t* len;        // [max_seqs] cached positions
+  int32_t* n_pend;     // [max_seqs] pending tokens not yet in the cache (1, or 2 for a draft that owes x_K)
+  int32_t* pend;       // [max_seqs][2]
+  int32_t* owned;      // [max_seqs] blocks owned
+  int32_t* table;      // [max_seqs][mbps] block ids
+  int32_t* free_stack; // [n_blocks]
+  int32_t* ctl;        // [0] free_top  [1] error flag  [2] arrival counter of the accept kernel
+  int32_t* mirror;     // host-mapped copy: [max_seqs][2] = (len, n_pend), then [2*max_seqs] = error flag
+  void* pool;
+  int n_blocks, bt, mbps, max_seqs, pcap;
+  int n_layers, nkv, hd;
+};
+
+// Element offset of (layer, which(0=K,1=V), block, kv head, token in block, 0) in the pool.
+__device__ __forceinline__ size_t kv_offset(const KvView& kv, int layer, int which, int blk, int head, int tok) {
+  return ((((size_t)(layer * 2 + which) * kv.n_blocks + blk) * kv.nkv + head) * kv.bt + tok) * (size_t)kv.hd;
+}
+
+__device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Make `seq` own the blocks that cover `tokens` positions (one thread).
+__device__ inline void kv_reserve(const KvView& kv, int seq, int tokens) {
+  const int need = ceil_div(tokens, kv.bt);
+  int own = kv.owned[seq];
+  int top = kv.ctl[0];
+  while (own < need) {
+    if (top <= 0 || own >= kv.mbps) { kv.ctl[1] = 1; break; }
+    kv.table[seq * kv.mbps + own] = kv.free_stack[--top];
+    ++own;
+  }
+  kv.owned[seq] = own;
+  kv.ctl[0] = top;
+}
+
+// Truncate `seq` to new_len positions, returning whole blocks past it, highest table index first (one thread).
+__device__ inline void kv_truncate(const KvView& kv, int seq, int new_len) {
+  const int keep = ceil_div(new_len, kv.bt);
+  int own = kv.owned[seq];
+  int top = kv.ctl[0];
+  while (own > keep) {
+    --own;
+    kv.free_stack[top++] = kv.table[seq * kv.mbps + own];
+    kv.table[seq * kv.mbps + own] = -1;
+  }
+  kv.owned[seq] = own;
+  kv.ctl[0] = top;
+  kv.len[seq] = new_len;
+}
+
+__device__ inline void kv_publish(const KvView& kv, int seq) {
+  kv.mirror[2 * seq] = kv.len[seq];
+  kv.mirror[2 * seq + 1] = kv.n_pend[seq];
+  kv.mirror[2 * kv.max_seqs] = kv.ctl[1];
+}
+
+// Rows of one forward: row m belongs to sequence seq0 + m / R at offset j = m % R.
+struct Rows {
+  int32_t* pos;      // [M] position of the row
+  int32_t* active;   // [M] 1 if the row's key/value is to be written
+  int M, R, seq0;
+};
+
+}  // namespace ssd

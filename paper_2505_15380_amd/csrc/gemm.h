@@ -1,0 +1,267 @@
+// Skinny GEMMs of the decoder: Y[M,N] = X[M,Kd] . W[N,Kd]^T with M = rows of one forward (<= 128).
+// At these M the work is weight streaming: every weight byte is read once, coalesced, and the
+// contraction runs on MFMA 16x16x32 bf16 tiles (rows padded to 16; padded rows cost nothing that matters).
+//
+// Work decomposition, identical for both storage types:
+//   a workgroup (4 waves) owns two 16-column tiles (t0 from W0, t1 from W1) and one global k-split;
+//   its waves split the k range between them, partial tiles are summed through LDS in a fixed order,
+//   and one thread per (row, col) applies the epilogue.  Nothing is accumulated with atomics, so every output
+//   element has one summation order that does not depend on M: a row computed alone (autoregressive step)
+//   and the same row computed among K+1 (verification) give the same bits.
+//
+// bf16 weights are pre-packed so that a wave reads one tile (16 out-features x 32 in-features) as 64
+// consecutive 16-byte pieces: piece l of tile (nt, kt) = W[nt*16 + l%16][kt*32 + 8*(l/16) .. +7], tiles ordered
+// [nt][kt].  That is exactly the B-operand fragment of the MFMA, so a weight goes from HBM to the matrix
+// core through one dwordx4 load and nothing else.
+#pragma once
+#include "common.h"
+
+namespace ssd {
+
+enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2 };
+
+struct GemmArgs {
+  const void* A;     // activations [M][lda]
+  int lda;
+  const void* W0;    // weight matrix of tile slot 0 (packed bf16, or canonical fp32 [N][K])
+  const void* W1;    // weight matrix of tile slot 1
+  int M, N, K;       // N = out features of one matrix (unpadded)
+  int gs;            // global k-splits
+  // EPI_PARTIAL: out[s][m][n]
+  float* out;
+  size_t out_split_stride;
+  int ldo;
+  // EPI_QKV: bias, rotary table, destination of q and of the cache rows
+  const float* bias;
+  const float2* rope;   // [pos][hd/2] (cos, sin)
+  Rows rows;
+  float* q;             // [M][nq*hd]
+  KvView kv;
+  int layer, nq;
+  // EPI_SWIGLU
+  void* act;            // [M][N]
+};
+
+// ------------------------------------------------------------------------------------------ epilogues
+template <int EPI, typename AT, typename KVT>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int t0, int t1, int split, int row, int col,
+                                              float v0, float v1) {
+  if (row >= g.M) return;
+  if (EPI == EPI_PARTIAL) {
+    float* o = g.out + (size_t)split * g.out_split_stride + (size_t)row * g.ldo;
+    const int n0 = t0 * 16 + col, n1 = t1 * 16 + col;
+    if (n0 < g.N) o[n0] = v0;
+    if (n1 < g.N) o[n1] = v1;
+  } else if (EPI == EPI_SWIGLU) {
+    const int n = t0 * 16 + col;
+    if (n < g.N) {
+      const float s = v0 / (1.0f + expf(-v0));
+      AT::st((typename AT::T*)g.act + (size_t)row * g.N + n, s * v1);
+    }
+  } else {  // EPI_QKV: the two tiles hold dims d and d + hd/2 of one head
+    const int hd = g.kv.hd, half = hd >> 1;
+    const int n0 = t0 * 16 + col;
+    const int head = n0 / hd, d = n0 - head * hd;
+    if (g.bias) { v0 += g.bias[n0]; v1 += g.bias[n0 + half]; }
+    const int nq = g.nq, nkv = g.kv.nkv;
+    const int pos = g.rows.pos[row];
+    if (head < nq + nkv) {
+      const float2 cs = g.rope[(size_t)pos * half + d];
+      const float r0 = v0 * cs.x - v1 * cs.y;
+      const float r1 = v1 * cs.x + v0 * cs.y;
+      v0 = r0; v1 = r1;
+    }
+    if (head < nq) {
+      float* qo = g.q + (size_t)row * nq * hd + head * hd + d;
+      qo[0] = v0; qo[half] = v1;
+    } else if (g.rows.active[row]) {
+      const int which = head < nq + nkv ? 0 : 1;
+      const int kvh = head - nq - which * nkv;
+      const int seq = g.rows.seq0 + row / g.rows.R;
+      const int blk = g.kv.table[seq * g.kv.mbps + pos / g.kv.bt];
+      if (blk >= 0) {
+        typename KVT::T* dst = (typename KVT::T*)g.kv.pool + kv_offset(g.kv, g.layer, which, blk, kvh, pos % g.kv.bt) + d;
+        KVT::st(dst, v0);
+        KVT::st(dst + half, v1);
+      }
+    }
+  }
+}
+
+template <int EPI>
+__device__ __forceinline__ bool gemm_tiles(const GemmArgs& g, int item, int hd, int& t0, int& t1, int& split) {
+  const int ntiles = (g.N + 15) >> 4;
+  if (EPI == EPI_PARTIAL) {
+    const int npairs = (ntiles + 1) >> 1;
+    split = item / npairs;
+    const int p = item - split * npairs;
+    t0 = 2 * p; t1 = 2 * p + 1;
+  } else if (EPI == EPI_SWIGLU) {
+    split = 0; t0 = item; t1 = item;
+  } else {
+    const int per_head = hd >> 5;              // pairs of tiles per head
+    const int head = item / per_head, i = item - head * per_head;
+    split = 0; t0 = head * (hd >> 4) + i; t1 = t0 + per_head;
+  }
+  return t0 < ntiles;
+}
+
+// Sum the four waves' partial tiles (fixed order) and run the epilogue: thread tid owns (row tid/16, col tid%16).
+template <int EPI, typename AT, typename KVT>
+__device__ __forceinline__ void gemm_reduce_tile(const GemmArgs& g, float (*red)[2][256], int t0, int t1, int split,
+                                                 int mt) {
+  const int tid = threadIdx.x;
+  const float v0 = (red[0][0][tid] + red[1][0][tid]) + (red[2][0][tid] + red[3][0][tid]);
+  const float v1 = (red[0][1][tid] + red[1][1][tid]) + (red[2][1][tid] + red[3][1][tid]);
+  gemm_epilogue<EPI, AT, KVT>(g, t0, t1, split, mt * 16 + (tid >> 4), tid & 15, v0, v1);
+}
+
+// --------------------------------------------------------------------------------------- bf16 / MFMA
+// grid.x = work items (tile pairs x global splits).  MT = 16-row tiles of M.
+template <int MT, int EPI, typename KVT>
+__global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
+  __shared__ float red[4][2][256];
+  int t0, t1, split;
+  if (!gemm_tiles<EPI>(g, blockIdx.x, g.kv.hd, t0, t1, split)) return;
+  const int ntiles = (g.N + 15) >> 4;
+  const bool has1 = (EPI != EPI_PARTIAL) || (t1 < ntiles);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int KT = g.K >> 5;
+  // k-tiles of this workgroup, then of this wave (contiguous ranges, earlier ranges get the remainder)
+  const int per_s = KT / g.gs, rem_s = KT - per_s * g.gs;
+  const int wg_b = split * per_s + min(split, rem_s), wg_n = per_s + (split < rem_s ? 1 : 0);
+  const int per_w = wg_n >> 2, rem_w = wg_n & 3;
+  const int kb = wg_b + wave * per_w + min(wave, rem_w), ke = kb + per_w + (wave < rem_w ? 1 : 0);
+
+  const u32x4* w0 = (const u32x4*)g.W0 + (size_t)t0 * KT * 64 + lane;
+  const u32x4* w1 = (const u32x4*)g.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
+  const bf16_t* A = (const bf16_t*)g.A;
+  const int arow = lane & 15, akoff = (lane >> 4) * 8;
+
+  f32x4 acc[MT][2];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) { acc[mt][0] = f32x4{0, 0, 0, 0}; acc[mt][1] = f32x4{0, 0, 0, 0}; }
+
+  constexpr int U = 4;
+  int kt = kb;
+  for (; kt + U <= ke; kt += U) {
+    u32x4 b0[U], b1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      b0[u] = __builtin_nontemporal_load(w0 + (size_t)(kt + u) * 64);
+      b1[u] = __builtin_nontemporal_load(w1 + (size_t)(kt + u) * 64);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 16 + arow;
+      u32x4 a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        a[u] = u32x4{0u, 0u, 0u, 0u};
+        if (row < g.M) a[u] = *(const u32x4*)(A + (size_t)row * g.lda + (kt + u) * 32 + akoff);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b0[u]), acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b1[u]), acc[mt][1], 0, 0, 0);
+      }
+    }
+  }
+  for (; kt < ke; ++kt) {
+    const u32x4 b0 = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
+    const u32x4 b1 = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int row = mt * 16 + arow;
+      u32x4 a = u32x4{0u, 0u, 0u, 0u};
+      if (row < g.M) a = *(const u32x4*)(A + (size_t)row * g.lda + kt * 32 + akoff);
+      const bf16x8 av = __builtin_bit_cast(bf16x8, a);
+      acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b0), acc[mt][0], 0, 0, 0);
+      acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b1), acc[mt][1], 0, 0, 0);
+    }
+  }
+  // accumulator register r of lane l is element (row 4*(l/16)+r, col l%16) of the 16x16 tile
+  const int obase = ((lane >> 4) * 4) * 16 + (lane & 15);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt * 16 < g.M) {
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        red[wave][0][obase + r * 16] = acc[mt][0][r];
+        red[wave][1][obase + r * 16] = acc[mt][1][r];
+      }
+      __syncthreads();
+      gemm_reduce_tile<EPI, BF16, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt);
+    }
+  }
+}
+
+// -------------------------------------------------------------------------------------- fp32 / VALU
+// Same decomposition for the fp32 parity configuration; weights canonical [N][K] fp32, K % 32 == 0.
+template <int EPI, typename KVT>
+__global__ void __launch_bounds__(BLOCK) k_gemm_f32(GemmArgs g) {
+  __shared__ float red[4][2][256];
+  int t0, t1, split;
+  if (!gemm_tiles<EPI>(g, blockIdx.x, g.kv.hd, t0, t1, split)) return;
+  const int ntiles = (g.N + 15) >> 4;
+  const bool has1 = (EPI != EPI_PARTIAL) || (t1 < ntiles);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int KT = g.K >> 5;
+  const int per_s = KT / g.gs, rem_s = KT - per_s * g.gs;
+  const int wg_b = split * per_s + min(split, rem_s), wg_n = per_s + (split < rem_s ? 1 : 0);
+  const int per_w = wg_n >> 2, rem_w = wg_n & 3;
+  const int kb = wg_b + wave * per_w + min(wave, rem_w), ke = kb + per_w + (wave < rem_w ? 1 : 0);
+  const int col = lane & 15, kg = lane >> 4;
+  const int n0 = min(t0 * 16 + col, g.N - 1), n1 = min((has1 ? t1 : t0) * 16 + col, g.N - 1);
+  const float* w0 = (const float*)g.W0 + (size_t)n0 * g.K;
+  const float* w1 = (const float*)g.W1 + (size_t)n1 * g.K;
+  const float* A = (const float*)g.A;
+  const int MTn = (g.M + 15) >> 4;
+  for (int mt = 0; mt < MTn; ++mt) {
+    float a0[16], a1[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
+    const int rows = min(16, g.M - mt * 16);
+    for (int k = kb * 32 + kg; k < ke * 32; k += 4) {
+      const float x0 = w0[k], x1 = w1[k];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (r < rows) {
+          const float a = A[(size_t)(mt * 16 + r) * g.lda + k];
+          a0[r] = fmaf(a, x0, a0[r]);
+          a1[r] = fmaf(a, x1, a1[r]);
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float s0 = a0[r], s1 = a1[r];
+      s0 += __shfl_xor(s0, 16, WAVE); s0 += __shfl_xor(s0, 32, WAVE);
+      s1 += __shfl_xor(s1, 16, WAVE); s1 += __shfl_xor(s1, 32, WAVE);
+      if (kg == 0) { red[wave][0][r * 16 + col] = s0; red[wave][1][r * 16 + col] = s1; }
+    }
+    __syncthreads();
+    gemm_reduce_tile<EPI, F32, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt);
+  }
+}
+
+// Repack a canonical bf16 matrix [N][K] into MFMA B-fragment tiles (see the top of this file).
+// One thread per 16-byte piece; rows >= N are zero.
+__global__ void k_pack_bf16(const bf16_t* __restrict__ w, uint4* __restrict__ out, int N, int K, int ntiles) {
+  const int KT = K >> 5;
+  const size_t total = (size_t)ntiles * KT * 64;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int l = (int)(i & 63);
+    const size_t tile = i >> 6;
+    const int kt = (int)(tile % KT), nt = (int)(tile / KT);
+    const int n = nt * 16 + (l & 15), k = kt * 32 + (l >> 4) * 8;
+    uint4 v = uint4{0, 0, 0, 0};
+    if (n < N) v = *(const uint4*)(w + (size_t)n * K + k);
+    out[i] = v;
+  }
+}
+
+}  // namespace ssd

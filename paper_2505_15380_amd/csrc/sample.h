@@ -1,0 +1,363 @@
+// Row kernels around the vocabulary: embedding gather + row bookkeeping, residual add + RMSNorm,
+// warp + softmax, and the acceptance / resampling / commit kernel (Eq. 5-6, Alg. 1).
+#pragma once
+#include "common.h"
+
+namespace ssd {
+
+// ------------------------------------------------------------------------------------------ rows + embed
+struct EmbedArgs {
+  KvView kv;
+  Rows rows;
+  int pcap;                 // pending slots at the head of each sequence's rows (0 for a prefill chunk)
+  int n_seqs;
+  const int32_t* tokens;    // explicit tokens [n_seqs][tok_stride] for rows j >= pcap
+  int tok_stride;
+  const void* embed;        // [n_embed][d]
+  int n_embed, d;
+  float* h;                 // [M][d]
+};
+
+// One workgroup per row: resolve the row's token and position, copy its embedding into the residual stream.
+// Workgroup 0 also reserves the cache blocks the forward will write (sequences in ascending order).
+template <typename WT>
+__global__ void __launch_bounds__(BLOCK) k_embed(EmbedArgs e) {
+  const int m = blockIdx.x;
+  const int brel = m / e.rows.R, j = m - brel * e.rows.R;
+  const int seq = e.rows.seq0 + brel;
+  const int npend = e.pcap ? e.kv.n_pend[seq] : 0;
+  const int off = e.pcap - npend;                          // leading rows that carry nothing
+  const int len = e.kv.len[seq];
+  int tok, pos, active;
+  if (j < off) { tok = e.kv.pend[seq * 2]; pos = len; active = 0; }
+  else {
+    pos = len + (j - off); active = 1;
+    tok = j < e.pcap ? e.kv.pend[seq * 2 + (j - off)] : e.tokens[(size_t)brel * e.tok_stride + (j - e.pcap)];
+  }
+  tok = min(max(tok, 0), e.n_embed - 1);
+  if (threadIdx.x == 0) { e.rows.pos[m] = pos; e.rows.active[m] = active; }
+  const typename WT::T* src = (const typename WT::T*)e.embed + (size_t)tok * e.d;
+  for (int i = threadIdx.x; i < e.d; i += BLOCK) e.h[(size_t)m * e.d + i] = WT::ld(src + i);
+  if (m == 0 && threadIdx.x == 0) {
+    for (int b = 0; b < e.n_seqs; ++b) {
+      const int s = e.rows.seq0 + b;
+      const int o = e.pcap ? e.pcap - e.kv.n_pend[s] : 0;
+      kv_reserve(e.kv, s, e.kv.len[s] + e.rows.R - o);
+    }
+  }
+}
+
+// h[m] += sum of the k-split partials of the previous GEMM (ascending split order); xn[m] = RMSNorm(h[m]) * gain.
+template <typename AT>
+__global__ void __launch_bounds__(BLOCK) k_add_norm(float* h, const float* part, int n_part, size_t part_stride,
+                                                    const float* gain, float eps, void* xn, int d) {
+  __shared__ float s4[4];
+  const int m = blockIdx.x;
+  float* hr = h + (size_t)m * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += BLOCK) {
+    float v = hr[i];
+    for (int s = 0; s < n_part; ++s) v += part[(size_t)s * part_stride + (size_t)m * d + i];
+    hr[i] = v;
+    ss = fmaf(v, v, ss);
+  }
+  const float tot = block_sum(ss, s4);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  typename AT::T* xr = (typename AT::T*)xn + (size_t)m * d;
+  for (int i = threadIdx.x; i < d; i += BLOCK) AT::st(xr + i, hr[i] * inv * gain[i]);
+}
+
+// ------------------------------------------------------------------------------------------ warp + softmax
+__device__ __forceinline__ uint32_t order_key(float f) {      // larger float <-> larger key
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+struct WarpArgs {
+  const float* logits;   // [rows][ld]
+  int ld, V;
+  float temperature;
+  int top_k, greedy;
+  float* probs;          // [rows][V] or strided
+  size_t probs_stride;
+};
+
+// One workgroup per row.  Top-k keeps exactly k entries: everything above the k-th largest value, and of the
+// entries equal to it the ones with the lowest indices.
+__global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
+  __shared__ float s4[4];
+  __shared__ int hist[256];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_krem, sh_idxmax;
+  const int tid = threadIdx.x;
+  const float* x = w.logits + (size_t)blockIdx.x * w.ld;
+  float* p = w.probs + (size_t)blockIdx.x * w.probs_stride;
+  const int V = w.V;
+
+  if (w.greedy) {                                            // one-hot at the arg-max, lowest index on ties
+    float best = -INFINITY; int bi = 0x7fffffff;
+    for (int i = tid; i < V; i += BLOCK) { const float v = x[i]; if (v > best) { best = v; bi = i; } }
+    const float mx = block_max(best, s4);
+    int cand = (best == mx) ? bi : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, WAVE));
+    __shared__ int c4[4];
+    if ((tid & 63) == 0) c4[tid >> 6] = cand;
+    __syncthreads();
+    const int arg = min(min(c4[0], c4[1]), min(c4[2], c4[3]));
+    for (int i = tid; i < V; i += BLOCK) p[i] = (i == arg) ? 1.0f : 0.0f;
+    return;
+  }
+
+  // threshold key of the top-k set (radix select, 8 bits per pass, most significant first)
+  uint32_t kth = 0;          // keep keys > kth, and keys == kth with index <= idxmax
+  int idxmax = 0x7fffffff;
+  const bool use_k = w.top_k > 0 && w.top_k < V;
+  if (use_k) {
+    if (tid == 0) { sh_prefix = 0; sh_krem = w.top_k; }
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      hist[tid] = 0;
+      __syncthreads();
+      const uint32_t prefix = sh_prefix;
+      const uint32_t himask = pass ? (0xFFFFFFFFu << (shift + 8)) : 0u;
+      for (int i = tid; i < V; i += BLOCK) {
+        const uint32_t k = order_key(x[i]);
+        if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int krem = sh_krem, dsel = 0;
+        for (int dgt = 255; dgt >= 0; --dgt) {
+          if (hist[dgt] >= krem) { dsel = dgt; break; }
+          krem -= hist[dgt];
+        }
+        sh_krem = krem;
+        sh_prefix = prefix | ((uint32_t)dsel << shift);
+      }
+      __syncthreads();
+    }
+    kth = sh_prefix;
+    const int need_eq = sh_krem;                             // entries equal to kth that survive (>= 1)
+    int eq = 0;
+    for (int i = tid; i < V; i += BLOCK) eq += (order_key(x[i]) == kth);
+    eq = wave_sum_i(eq);
+    __shared__ int e4[4];
+    if ((tid & 63) == 0) e4[tid >> 6] = eq;
+    __syncthreads();
+    const int n_eq = e4[0] + e4[1] + e4[2] + e4[3];
+    if (n_eq > need_eq) {                                    // a tie straddles the cut: rare, resolved serially
+      if (tid == 0) {
+        int seen = 0, im = V - 1;
+        for (int i = 0; i < V; ++i)
+          if (order_key(x[i]) == kth && ++seen == need_eq) { im = i; break; }
+        sh_idxmax = im;
+      }
+      __syncthreads();
+      idxmax = sh_idxmax;
+    }
+  }
+  const float invT_is_div = w.temperature;
+  float mx = -INFINITY;
+  for (int i = tid; i < V; i += BLOCK) {
+    const float v = x[i];
+    const uint32_t k = order_key(v);
+    const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
+    if (keep) mx = fmaxf(mx, v / invT_is_div);
+  }
+  mx = block_max(mx, s4);
+  float sum = 0.f;
+  for (int i = tid; i < V; i += BLOCK) {
+    const float v = x[i];
+    const uint32_t k = order_key(v);
+    const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
+    const float e = keep ? expf(v / invT_is_div - mx) : 0.f;
+    p[i] = e;
+    sum += e;
+  }
+  sum = block_sum(sum, s4);
+  for (int i = tid; i < V; i += BLOCK) p[i] = p[i] / sum;
+}
+
+// ------------------------------------------------------------------------------ acceptance + resampling
+struct AcceptArgs {
+  const float* pt;       // [B][K+1][V]
+  size_t pt_seq_stride;  // elements between sequences
+  const float* pd;       // [B][K][V]
+  const int32_t* x;      // [B][K]
+  const float* uniforms; // [B][K+1] or NULL -> Philox(seed, seq, step, slot)
+  uint64_t seed, step;
+  int slot_base;         // r_i uses slot slot_base + i - 1, the emitted token slot_base + K
+  int B, K, V;
+  float beta;
+  int32_t* n_acc;        // [B] (may be NULL)
+  int32_t* next_tok;     // [B*tok_stride]
+  int tok_stride;
+  int32_t* flags;        // [B] or NULL
+  // commit (kv.len == NULL: decisions only)
+  KvView kv;
+  int seq0;
+};
+
+// Fixed-point weight of the canonical sampler: floor(w * 2^40) for w in [0, 1].
+__device__ __forceinline__ unsigned long long fix40(float w) {
+  return (unsigned long long)((double)w * 1099511627776.0);
+}
+
+// One workgroup per sequence.
+//  1. lanes i < K: threshold min(1, pt_i(x_i)/pd_i(x_i)) + beta in fp32 (division only when pd > pt, so never by
+//     zero), accept iff r_i < threshold; n = number of leading accepts via a wave ballot.
+//  2. emitted token: inverse CDF over w_j = max(0, pt_{n+1}(j) - pd_{n+1}(j)) (n < K) or pt_{K+1}(j) (n == K), with the
+//     weights in 2^40 fixed point so that the total and the prefix sums are integers (no dependence on the
+//     summation tree): smallest j whose inclusive prefix exceeds floor(total * u).
+//  3. the last workgroup to finish commits every sequence in ascending order: len += pending + n, pending =
+//     emitted token, blocks past the new length go back to the free stack.
+__global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
+  __shared__ unsigned long long part[BLOCK];
+  __shared__ unsigned long long w4[4];
+  __shared__ int sh_n, sh_tok, sh_last;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int K = a.K, V = a.V;
+  const float* pt = a.pt + (size_t)b * a.pt_seq_stride;
+  const float* pd = a.pd + (size_t)b * K * V;
+  const uint32_t seq = (uint32_t)(a.seq0 + b);
+
+  if (tid < WAVE) {
+    bool acc = false;
+    if (tid < K) {
+      const int xi = min(max(a.x[b * K + tid], 0), V - 1);
+      const float ptx = pt[(size_t)tid * V + xi], pdx = pd[(size_t)tid * V + xi];
+      const float r = a.uniforms ? a.uniforms[b * (K + 1) + tid] : philox_uniform(a.seed, seq, a.step, a.slot_base + tid);
+      float thr;
+      if (pdx > ptx) thr = __fadd_rn(__fdiv_rn(ptx, pdx), a.beta);
+      else thr = __fadd_rn(1.0f, a.beta);
+      acc = r < thr;
+    }
+    const unsigned long long rej = ~__ballot(acc);          // lanes >= K vote "reject"
+    if (tid == 0) sh_n = min(__ffsll((long long)rej) - 1, K);
+  }
+  __syncthreads();
+  const int n = sh_n;
+  const float u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
+  const float* prow = pt + (size_t)n * V;
+  const float* drow = pd + (size_t)n * V;                   // only read when n < K
+  const int per = (V + BLOCK - 1) / BLOCK;                  // contiguous span of indices per thread
+  const int j0 = tid * per, j1 = min(j0 + per, V);
+  int fallback = 0;
+  bool residual = n < K;
+  unsigned long long total;
+  for (;;) {
+    unsigned long long s = 0;
+    for (int j = j0; j < j1; ++j) {
+      const float wgt = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
+      s += fix40(wgt);
+    }
+    part[tid] = s;
+    const unsigned long long ws = wave_sum_u64(s);
+    __syncthreads();
+    if ((tid & 63) == 0) w4[tid >> 6] = ws;
+    __syncthreads();
+    total = w4[0] + w4[1] + w4[2] + w4[3];
+    if (total == 0 && residual) { residual = false; fallback = 1; __syncthreads(); continue; }
+    break;
+  }
+  if (total == 0) {
+    if (tid == 0) sh_tok = 0;
+  } else {
+    const unsigned long long Ru = (unsigned long long)(u * 16777216.0f);
+    const unsigned long long tgt = (__umul64hi(total, Ru) << 40) | ((total * Ru) >> 24);   // floor(total*Ru / 2^24)
+    unsigned long long excl = 0;                             // sum of the spans before this thread's
+    for (int t = 0; t < tid; ++t) excl += part[t];
+    if (excl <= tgt && tgt < excl + part[tid]) {
+      unsigned long long c = excl;
+      int tok = j1 - 1;
+      for (int j = j0; j < j1; ++j) {
+        const float wgt = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
+        c += fix40(wgt);
+        if (c > tgt) { tok = j; break; }
+      }
+      sh_tok = tok;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    if (a.n_acc) a.n_acc[b] = n;
+    a.next_tok[(size_t)b * a.tok_stride] = sh_tok;
+    if (a.flags) a.flags[b] = fallback;
+  }
+  if (a.kv.len == nullptr) return;
+  // ---- commit by the last workgroup to arrive
+  if (tid == 0) {
+    __threadfence();
+    const int arrived = atomicAdd(&a.kv.ctl[2], 1);
+    sh_last = (arrived == a.B - 1);
+  }
+  __syncthreads();
+  if (!sh_last || tid != 0) return;
+  __threadfence();
+  for (int s = 0; s < a.B; ++s) {
+    const int sq = a.seq0 + s;
+    const int nn = a.n_acc ? ((volatile int32_t*)a.n_acc)[s] : 0;
+    const int tok = ((volatile int32_t*)a.next_tok)[(size_t)s * a.tok_stride];
+    kv_truncate(a.kv, sq, a.kv.len[sq] + a.kv.n_pend[sq] + nn);
+    a.kv.pend[sq * 2] = tok;
+    a.kv.n_pend[sq] = 1;
+    kv_publish(a.kv, sq);
+  }
+  a.kv.ctl[2] = 0;
+}
+
+// ------------------------------------------------------------------------------------------ small state kernels
+// Truncate one sequence and (optionally) set its pending token from a value or from device memory.
+__global__ void k_kv_set(KvView kv, int seq, int new_len, int add_len, int set_pending, int pending_value,
+                         const int32_t* pending_ptr) {
+  if (threadIdx.x || blockIdx.x) return;
+  const int target = new_len >= 0 ? new_len : kv.len[seq] + add_len;
+  kv_truncate(kv, seq, target);
+  if (set_pending) {
+    kv.pend[seq * 2] = pending_ptr ? *pending_ptr : pending_value;
+    kv.n_pend[seq] = 1;
+  }
+  kv_publish(kv, seq);
+}
+
+// Draft cache after a verification of K drafts (see ssd_kv_follow).
+__global__ void k_kv_follow(KvView kv, int n_seqs, int K, const int32_t* n_acc, const int32_t* next_tok,
+                            const int32_t* x) {
+  if (threadIdx.x || blockIdx.x) return;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int n = n_acc[s];
+    if (n < K) {
+      kv_truncate(kv, s, kv.len[s] - (K - 1 - n));
+      kv.pend[s * 2] = next_tok[s];
+      kv.n_pend[s] = 1;
+    } else {
+      kv.pend[s * 2] = x[s * K + K - 1];
+      kv.pend[s * 2 + 1] = next_tok[s];
+      kv.n_pend[s] = 2;
+    }
+    kv_publish(kv, s);
+  }
+}
+
+__global__ void k_kv_init(KvView kv) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < kv.n_blocks) kv.free_stack[i] = kv.n_blocks - 1 - i;       // lowest id on top
+  if (i < kv.max_seqs) {
+    kv.len[i] = 0; kv.n_pend[i] = 0; kv.pend[2 * i] = 0; kv.pend[2 * i + 1] = 0; kv.owned[i] = 0;
+    kv.mirror[2 * i] = 0; kv.mirror[2 * i + 1] = 0;
+  }
+  if (i < kv.max_seqs * kv.mbps) kv.table[i] = -1;
+  if (i == 0) { kv.ctl[0] = kv.n_blocks; kv.ctl[1] = 0; kv.ctl[2] = 0; kv.mirror[2 * kv.max_seqs] = 0; }
+}
+
+// Rotary table: (cos, sin)(pos * base^(-2i/hd)) evaluated in fp64, rounded once to fp32.
+__global__ void k_rope_table(float2* tab, int max_pos, int half, double base) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= max_pos * half) return;
+  const int pos = i / half, f = i - pos * half;
+  const double ang = (double)pos * pow(base, -(double)f / (double)half);
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+}  // namespace ssd

@@ -1,0 +1,695 @@
+// libssd: host side of the C ABI declared in include/ssd.h.  Validates arguments, carves the caller's
+// workspaces, and enqueues the kernels of one forward / acceptance step on the caller's stream.
+#include "../../include/ssd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "attention.h"
+#include "common.h"
+#include "gemm.h"
+#include "sample.h"
+
+using namespace ssd;
+
+// ------------------------------------------------------------------------------------------------ errors
+static thread_local std::string g_err;
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) return fail(SSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+#define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
+
+extern "C" const char* ssd_strerror(int code) {
+  switch (code) {
+    case SSD_OK: return "ok";
+    case SSD_EINVAL: return "invalid argument";
+    case SSD_ENOMEM: return "out of pool or buffer space";
+    case SSD_EHIP: return "HIP error";
+    case SSD_ENOSUP: return "unsupported shape";
+    default: return "unknown error";
+  }
+}
+extern "C" const char* ssd_last_error(void) { return g_err.c_str(); }
+
+// ------------------------------------------------------------------------------------------------ carving
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  template <typename T>
+  T* take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+  size_t size() const { return (off + 255) & ~(size_t)255; }
+};
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------------------------------------ model
+struct LayerW {
+  const float *ln1, *bqkv, *ln2;
+  const void *wqkv, *wo, *wgate, *wup, *wdown;
+};
+struct ssd_model {
+  ssd_model_config c;
+  int max_positions;
+  const void* embed;
+  const float* final_norm;
+  const void* head;
+  std::vector<LayerW> layers;
+  const float2* rope;
+  size_t esize() const { return c.dtype == SSD_DTYPE_BF16 ? 2 : 4; }
+  int n_qkv() const { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
+};
+
+static size_t mat_elems(const ssd_model_config& c, int N, int K) {   // elements a matrix takes in the model workspace
+  return c.dtype == SSD_DTYPE_BF16 ? (size_t)cdiv(N, 16) * 16 * K : (size_t)N * K;
+}
+
+static int check_config(const ssd_model_config* c, int max_positions) {
+  if (!c) return fail(SSD_EINVAL, "null config");
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 1 || c->vocab < 1 ||
+      c->n_embed < c->vocab || max_positions < 1 || !(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f))
+    return fail(SSD_EINVAL, "bad model dimensions");
+  if (c->dtype != SSD_DTYPE_FP32 && c->dtype != SSD_DTYPE_BF16) return fail(SSD_EINVAL, "bad dtype %d", c->dtype);
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return fail(SSD_ENOSUP, "head_dim must be 32, 64 or 128");
+  if (c->n_q_heads % c->n_kv_heads) return fail(SSD_ENOSUP, "n_q_heads must be a multiple of n_kv_heads");
+  if (c->d_model % 32 || (c->n_q_heads * c->head_dim) % 32 || c->d_ffn % 32)
+    return fail(SSD_ENOSUP, "d_model, n_q_heads*head_dim and d_ffn must be multiples of 32");
+  if (c->vocab > 16384) return fail(SSD_ENOSUP, "vocab > 16384");
+  return SSD_OK;
+}
+
+// Lays the model workspace out; with base == nullptr only measures it.
+static size_t model_layout(const ssd_model_config& c, int max_positions, void* base, ssd_model* m) {
+  Carver cv(base);
+  const size_t es = c.dtype == SSD_DTYPE_BF16 ? 2 : 4;
+  const int d = c.d_model, nqkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, nqd = c.n_q_heads * c.head_dim;
+  auto mat = [&](int N, int K) { return (const void*)cv.take<char>(mat_elems(c, N, K) * es); };
+  const void* embed = cv.take<char>((size_t)c.n_embed * d * es);
+  const float* fn = cv.take<float>(d);
+  const void* head = mat(c.vocab, d);
+  const float2* rope = cv.take<float2>((size_t)max_positions * (c.head_dim / 2));
+  if (m) { m->embed = embed; m->final_norm = fn; m->head = head; m->rope = rope; m->layers.resize(c.n_layers); }
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerW w;
+    w.ln1 = cv.take<float>(d);
+    w.wqkv = mat(nqkv, d);
+    w.bqkv = cv.take<float>(nqkv);
+    w.wo = mat(d, nqd);
+    w.ln2 = cv.take<float>(d);
+    w.wgate = mat(c.d_ffn, d);
+    w.wup = mat(c.d_ffn, d);
+    w.wdown = mat(d, c.d_ffn);
+    if (!c.qkv_bias) w.bqkv = nullptr;
+    if (m) m->layers[l] = w;
+  }
+  return cv.size();
+}
+
+extern "C" size_t ssd_model_workspace_bytes(const ssd_model_config* cfg, int max_positions) {
+  if (check_config(cfg, max_positions) != SSD_OK) return 0;
+  return model_layout(*cfg, max_positions, nullptr, nullptr);
+}
+
+static int put_matrix(const ssd_model_config& c, const void* src, const void* dst, int N, int K, hipStream_t st) {
+  if (c.dtype == SSD_DTYPE_BF16) {
+    const int ntiles = cdiv(N, 16);
+    const size_t pieces = (size_t)ntiles * (K / 32) * 64;
+    const int blocks = (int)std::min<size_t>((pieces + 255) / 256, 65535);
+    hipLaunchKernelGGL(k_pack_bf16, dim3(blocks), dim3(256), 0, st, (const bf16_t*)src, (uint4*)dst, N, K, ntiles);
+    LAUNCH_CHECK();
+  } else {
+    HIP_TRY(hipMemcpyAsync((void*)dst, src, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st));
+  }
+  return SSD_OK;
+}
+
+extern "C" int ssd_model_create(const ssd_model_config* cfg, const void* const* dev_weights, int n_weights,
+                                int max_positions, void* dev_model_ws, size_t ws_bytes, void* stream, ssd_model** out) {
+  int rc = check_config(cfg, max_positions);
+  if (rc) return rc;
+  if (!dev_weights || !dev_model_ws || !out) return fail(SSD_EINVAL, "null argument");
+  if (n_weights != 3 + 8 * cfg->n_layers) return fail(SSD_EINVAL, "expected %d weight pointers, got %d", 3 + 8 * cfg->n_layers, n_weights);
+  for (int i = 0; i < n_weights; ++i) {
+    const bool is_bias = i >= 3 && (i - 3) % 8 == 2;
+    if (!dev_weights[i] && !(is_bias && !cfg->qkv_bias)) return fail(SSD_EINVAL, "weight pointer %d is null", i);
+  }
+  if ((uintptr_t)dev_model_ws & 255) return fail(SSD_EINVAL, "model workspace must be 256-byte aligned");
+  const size_t need = model_layout(*cfg, max_positions, nullptr, nullptr);
+  if (ws_bytes < need) return fail(SSD_ENOMEM, "model workspace: need %zu bytes, got %zu", need, ws_bytes);
+  ssd_model* m = new (std::nothrow) ssd_model();
+  if (!m) return fail(SSD_ENOMEM, "host allocation failed");
+  m->c = *cfg;
+  m->max_positions = max_positions;
+  model_layout(*cfg, max_positions, dev_model_ws, m);
+  hipStream_t st = (hipStream_t)stream;
+  const ssd_model_config& c = *cfg;
+  const size_t es = m->esize();
+  const int d = c.d_model, nqkv = m->n_qkv(), nqd = c.n_q_heads * c.head_dim;
+#define TRY_RC(x) do { rc = (x); if (rc) { delete m; return rc; } } while (0)
+#define COPY(dst, src, bytes) do { hipError_t e_ = hipMemcpyAsync((void*)(dst), (src), (bytes), hipMemcpyDeviceToDevice, st); \
+    if (e_ != hipSuccess) { delete m; return fail(SSD_EHIP, "copy of weights: %s", hipGetErrorString(e_)); } } while (0)
+  COPY(m->embed, dev_weights[0], (size_t)c.n_embed * d * es);
+  COPY(m->final_norm, dev_weights[1], (size_t)d * 4);
+  TRY_RC(put_matrix(c, dev_weights[2], m->head, c.vocab, d, st));
+  for (int l = 0; l < c.n_layers; ++l) {
+    const void* const* w = dev_weights + 3 + 8 * l;
+    const LayerW& L = m->layers[l];
+    COPY(L.ln1, w[0], (size_t)d * 4);
+    TRY_RC(put_matrix(c, w[1], L.wqkv, nqkv, d, st));
+    if (c.qkv_bias) COPY(L.bqkv, w[2], (size_t)nqkv * 4);
+    TRY_RC(put_matrix(c, w[3], L.wo, d, nqd, st));
+    COPY(L.ln2, w[4], (size_t)d * 4);
+    TRY_RC(put_matrix(c, w[5], L.wgate, c.d_ffn, d, st));
+    TRY_RC(put_matrix(c, w[6], L.wup, c.d_ffn, d, st));
+    TRY_RC(put_matrix(c, w[7], L.wdown, d, c.d_ffn, st));
+  }
+  {
+    const int half = c.head_dim / 2, total = max_positions * half;
+    hipLaunchKernelGGL(k_rope_table, dim3(cdiv(total, 256)), dim3(256), 0, st, (float2*)m->rope, max_positions, half,
+                       (double)c.rope_base);
+    hipError_t e_ = hipGetLastError();
+    if (e_ != hipSuccess) { delete m; return fail(SSD_EHIP, "rope table: %s", hipGetErrorString(e_)); }
+  }
+#undef COPY
+#undef TRY_RC
+  *out = m;
+  return SSD_OK;
+}
+
+extern "C" int ssd_model_destroy(ssd_model* m) {
+  delete m;
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ kv
+constexpr int MAX_SPLITS = 16;   // capacity of the k-split partial buffer
+constexpr int MAX_ROWS = 128;
+
+struct ssd_kv {
+  const ssd_model* m;
+  KvView v;
+  int max_seqs, max_rows, NC;
+  // workspace
+  Rows rows;
+  float *h, *q, *o_part, *ml_part, *part, *logits, *probs;
+  void *xn, *attn, *act;
+  int32_t* scratch_i;              // [2 * max_seqs]: n_accepted / next_token when the caller passes none
+  // host
+  int32_t* mirror_host;
+  std::vector<int> len_ub, npend_ub;
+};
+
+static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_blocks, int mbps, void* base, ssd_kv* kv) {
+  const ssd_model_config& c = m->c;
+  Carver cv(base);
+  const int Mmax = max_seqs * max_rows;
+  const int NC = cdiv(m->max_positions, ATT_CHUNK);
+  const size_t es = m->esize();
+  const int nqd = c.n_q_heads * c.head_dim;
+  int32_t* len = cv.take<int32_t>(max_seqs);
+  int32_t* n_pend = cv.take<int32_t>(max_seqs);
+  int32_t* pend = cv.take<int32_t>(2 * max_seqs);
+  int32_t* owned = cv.take<int32_t>(max_seqs);
+  int32_t* table = cv.take<int32_t>((size_t)max_seqs * mbps);
+  int32_t* free_stack = cv.take<int32_t>(n_blocks);
+  int32_t* ctl = cv.take<int32_t>(4);
+  int32_t* rpos = cv.take<int32_t>(Mmax);
+  int32_t* ract = cv.take<int32_t>(Mmax);
+  int32_t* scratch_i = cv.take<int32_t>(2 * max_seqs);
+  float* h = cv.take<float>((size_t)Mmax * c.d_model);
+  void* xn = cv.take<char>((size_t)Mmax * c.d_model * es);
+  float* q = cv.take<float>((size_t)Mmax * nqd);
+  float* o_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * c.head_dim);
+  float* ml_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * 2);
+  void* attn = cv.take<char>((size_t)Mmax * nqd * es);
+  float* part = cv.take<float>((size_t)MAX_SPLITS * Mmax * c.d_model);
+  void* act = cv.take<char>((size_t)Mmax * c.d_ffn * es);
+  float* logits = cv.take<float>((size_t)Mmax * c.vocab);
+  float* probs = cv.take<float>((size_t)Mmax * c.vocab);
+  if (kv) {
+    kv->v.len = len; kv->v.n_pend = n_pend; kv->v.pend = pend; kv->v.owned = owned; kv->v.table = table;
+    kv->v.free_stack = free_stack; kv->v.ctl = ctl;
+    kv->rows.pos = rpos; kv->rows.active = ract;
+    kv->scratch_i = scratch_i;
+    kv->h = h; kv->xn = xn; kv->q = q; kv->o_part = o_part; kv->ml_part = ml_part; kv->attn = attn; kv->part = part;
+    kv->act = act; kv->logits = logits; kv->probs = probs;
+    kv->NC = NC;
+  }
+  return cv.size();
+}
+
+extern "C" size_t ssd_kv_pool_bytes(const ssd_model* m, int n_blocks, int block_tokens) {
+  if (!m || n_blocks < 1 || block_tokens < 1) return 0;
+  return (size_t)m->c.n_layers * 2 * n_blocks * m->c.n_kv_heads * block_tokens * m->c.head_dim * m->esize();
+}
+
+extern "C" size_t ssd_kv_workspace_bytes(const ssd_model* m, int max_seqs, int max_rows, int n_blocks, int mbps) {
+  if (!m || max_seqs < 1 || max_rows < 1 || n_blocks < 1 || mbps < 1) return 0;
+  return kv_layout(m, max_seqs, max_rows, n_blocks, mbps, nullptr, nullptr);
+}
+
+extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int n_blocks, int block_tokens, int mbps,
+                             int pending_cap, void* dev_pool, size_t pool_bytes, void* dev_ws, size_t ws_bytes,
+                             void* stream, ssd_kv** out) {
+  if (!m || !dev_pool || !dev_ws || !out) return fail(SSD_EINVAL, "null argument");
+  if (max_seqs < 1 || max_rows < 1 || n_blocks < 1 || block_tokens < 1 || mbps < 1)
+    return fail(SSD_EINVAL, "bad cache dimensions");
+  if (max_seqs * max_rows > MAX_ROWS) return fail(SSD_ENOSUP, "max_seqs*max_rows = %d exceeds %d", max_seqs * max_rows, MAX_ROWS);
+  if (pending_cap != 1 && pending_cap != 2) return fail(SSD_EINVAL, "pending_cap must be 1 or 2");
+  if (max_rows < pending_cap) return fail(SSD_EINVAL, "max_rows < pending_cap");
+  if (((uintptr_t)dev_pool & 255) || ((uintptr_t)dev_ws & 255)) return fail(SSD_EINVAL, "buffers must be 256-byte aligned");
+  const size_t need_pool = ssd_kv_pool_bytes(m, n_blocks, block_tokens);
+  if (pool_bytes < need_pool) return fail(SSD_ENOMEM, "KV pool: need %zu bytes, got %zu", need_pool, pool_bytes);
+  const size_t need_ws = kv_layout(m, max_seqs, max_rows, n_blocks, mbps, nullptr, nullptr);
+  if (ws_bytes < need_ws) return fail(SSD_ENOMEM, "KV workspace: need %zu bytes, got %zu", need_ws, ws_bytes);
+  ssd_kv* kv = new (std::nothrow) ssd_kv();
+  if (!kv) return fail(SSD_ENOMEM, "host allocation failed");
+  kv->m = m;
+  kv->max_seqs = max_seqs;
+  kv->max_rows = max_rows;
+  kv_layout(m, max_seqs, max_rows, n_blocks, mbps, dev_ws, kv);
+  KvView& v = kv->v;
+  v.pool = dev_pool;
+  v.n_blocks = n_blocks; v.bt = block_tokens; v.mbps = mbps; v.max_seqs = max_seqs; v.pcap = pending_cap;
+  v.n_layers = m->c.n_layers; v.nkv = m->c.n_kv_heads; v.hd = m->c.head_dim;
+  hipError_t e = hipHostMalloc((void**)&kv->mirror_host, (2 * max_seqs + 1) * sizeof(int32_t), hipHostMallocMapped);
+  if (e != hipSuccess) { delete kv; return fail(SSD_EHIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
+  memset(kv->mirror_host, 0, (2 * max_seqs + 1) * sizeof(int32_t));
+  e = hipHostGetDevicePointer((void**)&v.mirror, kv->mirror_host, 0);
+  if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)); }
+  kv->len_ub.assign(max_seqs, 0);
+  kv->npend_ub.assign(max_seqs, 0);
+  const int n = std::max(std::max(n_blocks, max_seqs * mbps), max_seqs);
+  hipLaunchKernelGGL(k_kv_init, dim3(cdiv(n, 256)), dim3(256), 0, (hipStream_t)stream, v);
+  e = hipGetLastError();
+  if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
+  *out = kv;
+  return SSD_OK;
+}
+
+extern "C" int ssd_kv_destroy(ssd_kv* kv) {
+  if (!kv) return SSD_OK;
+  if (kv->mirror_host) (void)hipHostFree(kv->mirror_host);
+  delete kv;
+  return SSD_OK;
+}
+
+// Bring the host's length bounds up to date with the device (synchronises the stream).
+static int kv_refresh(ssd_kv* kv, hipStream_t st) {
+  HIP_TRY(hipStreamSynchronize(st));
+  for (int s = 0; s < kv->max_seqs; ++s) {
+    kv->len_ub[s] = kv->mirror_host[2 * s];
+    kv->npend_ub[s] = kv->mirror_host[2 * s + 1];
+  }
+  if (kv->mirror_host[2 * kv->max_seqs]) return fail(SSD_ENOMEM, "device allocator reported pool exhaustion");
+  return SSD_OK;
+}
+
+// Can sequences [seq0, seq0+B) each take R more positions?  Uses the host's upper bounds; refreshes once
+// from the device before giving up.
+static int kv_check_room(ssd_kv* kv, int seq0, int B, int R, hipStream_t st) {
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    long blocks = 0;
+    bool ok = true;
+    for (int s = 0; s < kv->max_seqs; ++s) {
+      const bool in = s >= seq0 && s < seq0 + B;
+      const int tokens = kv->len_ub[s] + (in ? R : 0);
+      const int nb = cdiv(tokens, kv->v.bt);
+      if (in && (nb > kv->v.mbps || tokens > kv->m->max_positions)) ok = false;
+      blocks += nb;
+    }
+    if (ok && blocks <= kv->v.n_blocks) return SSD_OK;
+    if (attempt == 0) {
+      int rc = kv_refresh(kv, st);
+      if (rc) return rc;
+    }
+  }
+  return fail(SSD_ENOMEM, "KV cache cannot hold %d more positions for sequences %d..%d", R, seq0, seq0 + B - 1);
+}
+
+// ------------------------------------------------------------------------------------------------ forward
+template <typename DT, int EPI>
+static int launch_gemm(const ssd_model* m, GemmArgs g, int items, hipStream_t st) {
+  if (m->c.dtype == SSD_DTYPE_BF16) {
+    const int MT = cdiv(g.M, 16);
+    if (MT <= 1) hipLaunchKernelGGL((k_gemm_bf16<1, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
+    else if (MT <= 2) hipLaunchKernelGGL((k_gemm_bf16<2, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
+    else if (MT <= 4) hipLaunchKernelGGL((k_gemm_bf16<4, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<8, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
+  } else {
+    hipLaunchKernelGGL((k_gemm_f32<EPI, F32>), dim3(items), dim3(BLOCK), 0, st, g);
+  }
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+static int pick_splits(int K, int npairs) {
+  const int KT = K / 32;
+  int gs = std::max(1, 256 / std::max(1, npairs));
+  gs = std::min(gs, std::max(1, KT / 8));
+  return std::min(gs, MAX_SPLITS);
+}
+
+template <typename DT, int HD>
+static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, hipStream_t st) {
+  hipLaunchKernelGGL((k_attn_chunk<HD, DT>), dim3(nchunks, nkv, B), dim3(BLOCK), 0, st, a);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_attn_combine<HD, DT>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+// One decoder forward for sequences [seq0, seq0+B), R rows each.  pcap = pending slots at the head of each
+// sequence's rows (0: all rows take explicit tokens).  Leaves logits [B*R][vocab] in the workspace when
+// with_head.  The caller has checked room.
+template <typename DT>
+static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int pcap, const int32_t* dev_tokens,
+                   int tok_stride, bool with_head, hipStream_t st) {
+  const ssd_model_config& c = m->c;
+  const int M = B * R, d = c.d_model, hd = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
+  const int nqd = nq * hd, nqkv = m->n_qkv();
+  Rows rows = kv->rows;
+  rows.M = M; rows.R = R; rows.seq0 = seq0;
+
+  EmbedArgs e;
+  e.kv = kv->v; e.rows = rows; e.pcap = pcap; e.n_seqs = B; e.tokens = dev_tokens; e.tok_stride = tok_stride;
+  e.embed = m->embed; e.n_embed = c.n_embed; e.d = d; e.h = kv->h;
+  hipLaunchKernelGGL((k_embed<DT>), dim3(M), dim3(BLOCK), 0, st, e);
+  LAUNCH_CHECK();
+
+  int max_len = 0;
+  for (int s = seq0; s < seq0 + B; ++s) max_len = std::max(max_len, kv->len_ub[s]);
+  const int nchunks = cdiv(max_len + R, ATT_CHUNK);
+
+  GemmArgs g0;
+  memset(&g0, 0, sizeof g0);
+  g0.M = M; g0.kv = kv->v; g0.rows = rows; g0.nq = nq; g0.rope = m->rope;
+  const size_t part_stride = (size_t)M * d;
+  const int gs_o = pick_splits(nqd, cdiv(cdiv(d, 16), 2));
+  const int gs_d = pick_splits(c.d_ffn, cdiv(cdiv(d, 16), 2));
+  int n_part = 0;
+  int rc;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& L = m->layers[l];
+    hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride, L.ln1,
+                       c.rms_eps, kv->xn, d);
+    LAUNCH_CHECK();
+    GemmArgs g = g0;                                       // QKV + bias + rotary + cache write
+    g.A = kv->xn; g.lda = d; g.W0 = L.wqkv; g.W1 = L.wqkv; g.N = nqkv; g.K = d; g.gs = 1;
+    g.bias = L.bqkv; g.q = kv->q; g.layer = l;
+    if ((rc = launch_gemm<DT, EPI_QKV>(m, g, (nq + 2 * nkv) * (hd / 32), st))) return rc;
+
+    AttnArgs a;
+    a.q = kv->q; a.kv = kv->v; a.rows = rows; a.layer = l; a.nq = nq; a.scale = 1.0f / sqrtf((float)hd);
+    a.o_part = kv->o_part; a.ml_part = kv->ml_part; a.NC = kv->NC; a.out = kv->attn;
+    if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, st);
+    else if (hd == 64) rc = launch_attn<DT, 64>(a, nchunks, nkv, B, M, st);
+    else rc = launch_attn<DT, 128>(a, nchunks, nkv, B, M, st);
+    if (rc) return rc;
+
+    g = g0;                                                // output projection -> k-split partials
+    g.A = kv->attn; g.lda = nqd; g.W0 = L.wo; g.W1 = L.wo; g.N = d; g.K = nqd; g.gs = gs_o;
+    g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
+    if ((rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_o, st))) return rc;
+
+    hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, gs_o, part_stride, L.ln2,
+                       c.rms_eps, kv->xn, d);
+    LAUNCH_CHECK();
+
+    g = g0;                                                // gate / up + SwiGLU
+    g.A = kv->xn; g.lda = d; g.W0 = L.wgate; g.W1 = L.wup; g.N = c.d_ffn; g.K = d; g.gs = 1; g.act = kv->act;
+    if ((rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st))) return rc;
+
+    g = g0;                                                // down projection -> k-split partials
+    g.A = kv->act; g.lda = c.d_ffn; g.W0 = L.wdown; g.W1 = L.wdown; g.N = d; g.K = c.d_ffn; g.gs = gs_d;
+    g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
+    if ((rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st))) return rc;
+    n_part = gs_d;
+  }
+  if (!with_head) return SSD_OK;
+  hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride,
+                     m->final_norm, c.rms_eps, kv->xn, d);
+  LAUNCH_CHECK();
+  GemmArgs g = g0;
+  g.A = kv->xn; g.lda = d; g.W0 = m->head; g.W1 = m->head; g.N = c.vocab; g.K = d; g.gs = 1;
+  g.out = kv->logits; g.out_split_stride = 0; g.ldo = c.vocab;
+  return launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(c.vocab, 16), 2), st);
+}
+
+static int forward_any(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int pcap, const int32_t* dev_tokens,
+                       int tok_stride, bool with_head, hipStream_t st) {
+  return m->c.dtype == SSD_DTYPE_BF16 ? forward<BF16>(m, kv, seq0, B, R, pcap, dev_tokens, tok_stride, with_head, st)
+                                      : forward<F32>(m, kv, seq0, B, R, pcap, dev_tokens, tok_stride, with_head, st);
+}
+
+static int check_pair(const ssd_model* m, const ssd_kv* kv) {
+  if (!m || !kv) return fail(SSD_EINVAL, "null handle");
+  if (kv->m != m) return fail(SSD_EINVAL, "the cache was created for another model");
+  return SSD_OK;
+}
+
+static int check_sample(const ssd_sample_config* s) {
+  if (!s) return fail(SSD_EINVAL, "null sample config");
+  if (!(s->beta >= 0.0f)) return fail(SSD_EINVAL, "beta must be >= 0");
+  if (!s->greedy && !(s->temperature > 0.0f)) return fail(SSD_EINVAL, "temperature must be > 0");
+  if (s->top_k < 0) return fail(SSD_EINVAL, "top_k must be >= 0");
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ prefill
+extern "C" int ssd_prefill(ssd_model* m, ssd_kv* kv, int seq, const int32_t* dev_tokens, int n, void* stream) {
+  int rc = check_pair(m, kv);
+  if (rc) return rc;
+  if (!dev_tokens || n < 1) return fail(SSD_EINVAL, "prefill needs at least one token");
+  if (seq < 0 || seq >= kv->max_seqs) return fail(SSD_EINVAL, "sequence %d out of range", seq);
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, 0, 0, 0, 0, (const int32_t*)nullptr);
+  LAUNCH_CHECK();
+  kv->len_ub[seq] = 0;
+  kv->npend_ub[seq] = 0;
+  if ((rc = kv_check_room(kv, seq, 1, n - 1, st))) return rc;
+  const int chunk = std::min(kv->max_rows, MAX_ROWS);
+  for (int i = 0; i < n - 1; i += chunk) {
+    const int R = std::min(chunk, n - 1 - i);
+    if ((rc = forward_any(m, kv, seq, 1, R, 0, dev_tokens + i, 0, false, st))) return rc;
+    hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, R, 0, 0, (const int32_t*)nullptr);
+    LAUNCH_CHECK();
+    kv->len_ub[seq] += R;
+  }
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, 0, 1, 0, dev_tokens + (n - 1));
+  LAUNCH_CHECK();
+  kv->npend_ub[seq] = 1;
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ step
+// Forward + warp + acceptance + commit for sequences 0..B-1.
+static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, const float* dev_pd,
+                const ssd_sample_config* cfg, uint64_t step_ctr, int slot_base, int32_t* dev_n, int32_t* dev_next,
+                int next_stride, float* probs_out, size_t probs_seq_stride, bool probs_last_row_only,
+                float* logits_out, hipStream_t st) {
+  const ssd_model_config& c = m->c;
+  const int pcap = kv->v.pcap, R = pcap + K, M = B * R, V = c.vocab;
+  int rc;
+  if ((rc = kv_check_room(kv, 0, B, R, st))) return rc;
+  if ((rc = forward_any(m, kv, 0, B, R, pcap, dev_x, K, true, st))) return rc;
+  if (logits_out) HIP_TRY(hipMemcpyAsync(logits_out, kv->logits, (size_t)M * V * 4, hipMemcpyDeviceToDevice, st));
+
+  // rows that need a distribution: all K+1 of a verification, or the last row of a draft step
+  WarpArgs w;
+  w.ld = V; w.V = V; w.temperature = cfg->temperature; w.top_k = cfg->top_k; w.greedy = cfg->greedy;
+  AcceptArgs a;
+  memset(&a, 0, sizeof a);
+  if (probs_last_row_only) {
+    w.logits = kv->logits + (size_t)(R - 1) * V;
+    w.ld = R * V;                       // one row per sequence
+    w.probs = probs_out ? probs_out : kv->probs;
+    w.probs_stride = probs_out ? probs_seq_stride : (size_t)V;
+    hipLaunchKernelGGL(k_warp_softmax, dim3(B), dim3(BLOCK), 0, st, w);
+    a.pt = w.probs; a.pt_seq_stride = w.probs_stride;
+  } else {
+    w.logits = kv->logits + (size_t)(pcap - 1) * V;   // row of the last pending token, then the K drafts
+    // rows pcap-1 .. R-1 of every sequence are consecutive only when pcap == 1 (a target cache)
+    w.probs = probs_out ? probs_out : kv->probs;
+    w.probs_stride = V;
+    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(BLOCK), 0, st, w);
+    a.pt = w.probs; a.pt_seq_stride = (size_t)(K + 1) * V;
+  }
+  LAUNCH_CHECK();
+  a.pd = dev_pd; a.x = dev_x; a.uniforms = nullptr; a.seed = cfg->seed; a.step = step_ctr;
+  a.B = B; a.K = K; a.V = V; a.beta = cfg->beta;
+  a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
+  a.kv = kv->v; a.seq0 = 0;
+  a.slot_base = slot_base;
+  hipLaunchKernelGGL(k_accept, dim3(B), dim3(BLOCK), 0, st, a);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+extern "C" int ssd_verify(ssd_model* target, ssd_kv* kv, int n_seqs, const int32_t* prefix_len,
+                          const int32_t* dev_draft_tokens, const float* dev_draft_probs, int K,
+                          const ssd_sample_config* cfg, uint64_t step_ctr, int32_t* dev_n_accepted,
+                          int32_t* dev_next_token, float* dev_target_probs_opt, float* dev_logits_opt, void* stream) {
+  int rc = check_pair(target, kv);
+  if (rc) return rc;
+  if ((rc = check_sample(cfg))) return rc;
+  if (kv->v.pcap != 1) return fail(SSD_EINVAL, "ssd_verify needs a target cache (pending_cap 1)");
+  if (n_seqs < 1 || n_seqs > kv->max_seqs) return fail(SSD_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (K < 0 || K > SSD_MAX_K || K + 1 > kv->max_rows) return fail(SSD_EINVAL, "K = %d out of range (max_rows %d)", K, kv->max_rows);
+  if (K > 0 && (!dev_draft_tokens || !dev_draft_probs)) return fail(SSD_EINVAL, "draft tokens / probabilities are null");
+  if (!dev_n_accepted || !dev_next_token) return fail(SSD_EINVAL, "output pointers are null");
+  hipStream_t st = (hipStream_t)stream;
+  if (prefix_len) {
+    if ((rc = kv_refresh(kv, st))) return rc;
+    for (int s = 0; s < n_seqs; ++s)
+      if (prefix_len[s] != kv->len_ub[s] || kv->npend_ub[s] != 1)
+        return fail(SSD_EINVAL, "sequence %d: prefix_len %d but the cache holds %d positions (%d pending)", s,
+                    prefix_len[s], kv->len_ub[s], kv->npend_ub[s]);
+  }
+  rc = step(target, kv, n_seqs, K, dev_draft_tokens, dev_draft_probs, cfg, step_ctr, 0, dev_n_accepted, dev_next_token,
+            1, dev_target_probs_opt, 0, false, dev_logits_opt, st);
+  if (rc) return rc;
+  for (int s = 0; s < n_seqs; ++s) { kv->len_ub[s] += K + 1; kv->npend_ub[s] = 1; }
+  return SSD_OK;
+}
+
+extern "C" int ssd_draft_step(ssd_model* draft, ssd_kv* kv_d, int n_seqs, const ssd_sample_config* cfg,
+                              uint64_t step_ctr, int draft_idx, int32_t* dev_token_out, int token_stride,
+                              float* dev_probs_out, size_t probs_stride, void* stream) {
+  int rc = check_pair(draft, kv_d);
+  if (rc) return rc;
+  if ((rc = check_sample(cfg))) return rc;
+  if (n_seqs < 1 || n_seqs > kv_d->max_seqs) return fail(SSD_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (draft_idx < 0 || draft_idx > SSD_MAX_K) return fail(SSD_EINVAL, "draft_idx out of range");
+  if (!dev_token_out || token_stride < 1) return fail(SSD_EINVAL, "token output is null");
+  if (dev_probs_out && probs_stride < (size_t)draft->c.vocab) return fail(SSD_EINVAL, "probs_stride < vocab");
+  if (kv_d->max_rows < kv_d->v.pcap) return fail(SSD_EINVAL, "cache rows too small");
+  hipStream_t st = (hipStream_t)stream;
+  // the token is drawn with the uniform of slot `draft_idx` of this cycle: pass it as the step's only slot
+  ssd_sample_config c2 = *cfg;
+  c2.beta = 0.0f;
+  rc = step(draft, kv_d, n_seqs, 0, nullptr, nullptr, &c2, step_ctr, draft_idx, nullptr, dev_token_out, token_stride,
+            dev_probs_out, probs_stride, true, nullptr, st);
+  if (rc) return rc;
+  for (int s = 0; s < n_seqs; ++s) { kv_d->len_ub[s] += kv_d->npend_ub[s]; kv_d->npend_ub[s] = 1; }
+  return SSD_OK;
+}
+
+extern "C" int ssd_kv_rollback(ssd_kv* kv, int seq, int new_len, int pending_token, void* stream) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  if (seq < 0 || seq >= kv->max_seqs) return fail(SSD_EINVAL, "sequence %d out of range", seq);
+  hipStream_t st = (hipStream_t)stream;
+  if (new_len < 0 || new_len > kv->len_ub[seq]) {
+    int rc = kv_refresh(kv, st);
+    if (rc) return rc;
+    if (new_len < 0 || new_len > kv->len_ub[seq])
+      return fail(SSD_EINVAL, "rollback to %d but sequence %d holds %d positions", new_len, seq, kv->len_ub[seq]);
+  }
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, new_len, 0, 1, pending_token, (const int32_t*)nullptr);
+  LAUNCH_CHECK();
+  kv->len_ub[seq] = new_len;
+  kv->npend_ub[seq] = 1;
+  return SSD_OK;
+}
+
+extern "C" int ssd_kv_follow(ssd_kv* kv_d, int n_seqs, int K, const int32_t* dev_n_accepted,
+                             const int32_t* dev_next_token, const int32_t* dev_draft_tokens, void* stream) {
+  if (!kv_d || !dev_n_accepted || !dev_next_token || !dev_draft_tokens) return fail(SSD_EINVAL, "null argument");
+  if (kv_d->v.pcap != 2) return fail(SSD_EINVAL, "ssd_kv_follow needs a draft cache (pending_cap 2)");
+  if (n_seqs < 1 || n_seqs > kv_d->max_seqs || K < 1 || K > SSD_MAX_K) return fail(SSD_EINVAL, "bad n_seqs / K");
+  hipLaunchKernelGGL(k_kv_follow, dim3(1), dim3(1), 0, (hipStream_t)stream, kv_d->v, n_seqs, K, dev_n_accepted,
+                     dev_next_token, dev_draft_tokens);
+  LAUNCH_CHECK();
+  for (int s = 0; s < n_seqs; ++s) kv_d->npend_ub[s] = 2;       // the length can only have shrunk
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ pieces
+extern "C" int ssd_verify_from_probs(const float* dev_pt, const float* dev_pd, const int32_t* dev_tokens,
+                                     const float* dev_uniforms, int B, int K, int V, float beta,
+                                     int32_t* dev_n_accepted, int32_t* dev_next_token, int32_t* dev_flags, void* stream) {
+  if (!dev_pt || !dev_uniforms || !dev_n_accepted || !dev_next_token) return fail(SSD_EINVAL, "null argument");
+  if (B < 1 || K < 0 || K > SSD_MAX_K || V < 1 || V > 16384) return fail(SSD_EINVAL, "bad B / K / V");
+  if (K > 0 && (!dev_pd || !dev_tokens)) return fail(SSD_EINVAL, "draft tokens / probabilities are null");
+  if (!(beta >= 0.0f)) return fail(SSD_EINVAL, "beta must be >= 0");
+  AcceptArgs a;
+  memset(&a, 0, sizeof a);
+  a.pt = dev_pt; a.pt_seq_stride = (size_t)(K + 1) * V; a.pd = dev_pd; a.x = dev_tokens; a.uniforms = dev_uniforms;
+  a.B = B; a.K = K; a.V = V; a.beta = beta; a.n_acc = dev_n_accepted; a.next_tok = dev_next_token; a.tok_stride = 1;
+  a.flags = dev_flags;
+  hipLaunchKernelGGL(k_accept, dim3(B), dim3(BLOCK), 0, (hipStream_t)stream, a);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+extern "C" int ssd_warp_probs(const float* dev_logits, int rows, int V, const ssd_sample_config* cfg, float* dev_probs,
+                              void* stream) {
+  int rc = check_sample(cfg);
+  if (rc) return rc;
+  if (!dev_logits || !dev_probs || rows < 1 || V < 1 || V > 16384) return fail(SSD_EINVAL, "bad argument");
+  WarpArgs w;
+  w.logits = dev_logits; w.ld = V; w.V = V; w.temperature = cfg->temperature; w.top_k = cfg->top_k; w.greedy = cfg->greedy;
+  w.probs = dev_probs; w.probs_stride = V;
+  hipLaunchKernelGGL(k_warp_softmax, dim3(rows), dim3(BLOCK), 0, (hipStream_t)stream, w);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ state
+extern "C" int ssd_kv_state(ssd_kv* kv, int seq, void* stream, int32_t* len, int32_t* n_pending, int32_t pending[2],
+                            int32_t* n_owned, int32_t* block_table, int block_table_cap) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  if (seq < 0 || seq >= kv->max_seqs) return fail(SSD_EINVAL, "sequence %d out of range", seq);
+  hipStream_t st = (hipStream_t)stream;
+  int rc = kv_refresh(kv, st);
+  if (rc && rc != SSD_ENOMEM) return rc;
+  int32_t own = 0;
+  HIP_TRY(hipMemcpy(&own, kv->v.owned + seq, 4, hipMemcpyDeviceToHost));
+  if (len) *len = kv->len_ub[seq];
+  if (n_pending) *n_pending = kv->npend_ub[seq];
+  if (pending) HIP_TRY(hipMemcpy(pending, kv->v.pend + 2 * seq, 8, hipMemcpyDeviceToHost));
+  if (n_owned) *n_owned = own;
+  if (block_table) {
+    if (block_table_cap < own) return fail(SSD_ENOMEM, "block_table_cap %d < %d owned blocks", block_table_cap, own);
+    if (own) HIP_TRY(hipMemcpy(block_table, kv->v.table + (size_t)seq * kv->v.mbps, (size_t)own * 4, hipMemcpyDeviceToHost));
+  }
+  return SSD_OK;
+}
+
+extern "C" int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, int32_t* n_free,
+                                 int32_t* dev_error_flag) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  int32_t ctl[4];
+  HIP_TRY(hipMemcpy(ctl, kv->v.ctl, sizeof ctl, hipMemcpyDeviceToHost));
+  if (n_free) *n_free = ctl[0];
+  if (dev_error_flag) *dev_error_flag = ctl[1];
+  if (free_stack) {
+    if (cap < ctl[0]) return fail(SSD_ENOMEM, "cap %d < %d free blocks", cap, ctl[0]);
+    if (ctl[0]) HIP_TRY(hipMemcpy(free_stack, kv->v.free_stack, (size_t)ctl[0] * 4, hipMemcpyDeviceToHost));
+  }
+  return SSD_OK;
+}
