@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD hot path on one MI355X.
+
+A step is one SSD cycle of Alg. 1 at batch 1 on the 0.5B-shaped workload: K=4 draft steps (Eq. 2-3), one
+parallel verification of the K+1 rows (Eq. 4) with acceptance / resampling (Eq. 5-6) and the cache commit,
+and the draft cache following the decision.  `value` is emitted speech tokens per second over whole cycles,
+inputs resident in HBM.  Extra keys report the verification alone (latency, fraction of HBM peak), the same
+GPU's plain autoregressive decoding, the roofline of the dominant kernel and the CPU oracle timed beside it."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(shape, K, L, n_seqs=1):
+    """Bytes one verification must move: every weight matrix once, the cached keys/values of the prefix once,
+    the K+1 new key/value rows, and the logits / probability rows (2K+1 rows of V fp32)."""
+    es = 2 if shape["dtype"] == "bf16" else 4
+    d, hd, nq, nkv, ffn, V = (shape[k] for k in ("d_model", "head_dim", "n_q_heads", "n_kv_heads", "d_ffn", "vocab"))
+    per_layer = d * (nq + 2 * nkv) * hd + nq * hd * d + 3 * d * ffn
+    weights = (shape["n_layers"] * per_layer + V * d) * es
+    kv_tok = 2 * nkv * hd * es * shape["n_layers"]
+    return weights + n_seqs * (L + K + 1) * kv_tok + n_seqs * (2 * K + 1) * V * 4, weights
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--beta", type=float, default=0.4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_15380_amd as ssd
+    import synth_inputs as si
+
+    wl = si.workload("half_b_k4")
+    K = wl["K"]
+    tshape, dshape = si.model_shape(wl["target"]), si.model_shape(wl["draft"])
+    tw = si.make_weights(tshape, wl["seeds"]["target"])
+    dw = si.make_weights(dshape, wl["seeds"]["draft"])
+    prefix = si.make_prefix(tshape, *wl["prefix"], wl["seeds"]["prefix"])
+    L0 = len(prefix) - 1
+    steps, warmup = args.steps, args.warmup
+    max_pos = len(prefix) + (steps + warmup + 8) * (K + 1) + 64
+    cfg = ssd.sample_config(beta=args.beta, temperature=wl["temperature"], top_k=wl["top_k"], seed=wl["seeds"]["rng"])
+    dcfg = ssd.sample_config(temperature=wl["temperature"], top_k=wl["top_k"], seed=wl["seeds"]["rng"] + 1)
+    sess = ssd.SSDSession(tshape, tw, dshape, dw, 1, K, max_pos, cfg, dcfg)
+    dev_prefix = torch.from_numpy(prefix).cuda()
+    sess.prefill(0, dev_prefix)
+    torch.cuda.synchronize()
+
+    # ---- timed region: whole SSD cycles ------------------------------------------------------------
+    n_log = torch.zeros((warmup + steps, 1), dtype=torch.int32, device="cuda")
+    t_log = torch.zeros((warmup + steps, 1), dtype=torch.int32, device="cuda")
+    for s in range(warmup):
+        sess.cycle(s, out=dict(n_accepted=n_log[s], next_token=t_log[s], probs=None, logits=None))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(warmup, warmup + steps):
+        sess.cycle(s, out=dict(n_accepted=n_log[s], next_token=t_log[s], probs=None, logits=None))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_acc = n_log[warmup:].cpu().numpy().ravel()
+    emitted = int((n_acc + 1).sum())
+    value = emitted / dt
+
+    # ---- verification alone at the nominal prefix length, HIP events on the launch stream ------------
+    stream = torch.cuda.current_stream()
+
+    def time_loop(fn, iters):
+        for i in range(5):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(iters):
+            fn(i)
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    pend = int(prefix[-1])
+
+    def verify_once(i):
+        ssd.ssd_kv_rollback(sess.kv, 0, L0, pend)
+        ssd.ssd_verify(sess.target, sess.kv, 1, sess.x, sess.pd, K, cfg, 10_000 + i,
+                       out=dict(n_accepted=sess.n_acc, next_token=sess.next, probs=None, logits=None))
+
+    def ar_once(i):
+        ssd.ssd_kv_rollback(sess.kv, 0, L0, pend)
+        sess.ar_step(20_000 + i)
+
+    def draft_once(i):
+        ssd.ssd_kv_rollback(sess.kv_d, 0, L0, pend)
+        ssd.ssd_draft_step(sess.draft, sess.kv_d, 1, dcfg, 30_000 + i, 0, sess.x[:, 0], K, sess.pd[:, 0], K * sess.V)
+
+    def rollback_only(i):
+        ssd.ssd_kv_rollback(sess.kv, 0, L0, pend)
+
+    iters = max(20, min(200, steps))
+    rb_ms = time_loop(rollback_only, iters)
+    verify_ms = time_loop(verify_once, iters) - rb_ms
+    ar_ms = time_loop(ar_once, iters) - rb_ms
+    draft_ms = time_loop(draft_once, iters) - rb_ms
+    abytes, wbytes = algorithmic_bytes(tshape, K, L0)
+    verify_gbs = abytes / (verify_ms * 1e-3) / 1e9
+
+    # ---- dominant kernel (gate/up GEMM + SwiGLU): events around each of its launches -------------------
+    ssd.ssd_profile_begin("gate_up")
+    for i in range(20):
+        verify_once(i)
+    k_ms, k_n = ssd.ssd_profile_end()
+    gu_bytes = 2 * tshape["d_model"] * tshape["d_ffn"] * 2                 # gate + up matrices, bf16, per launch
+    gu_ms = k_ms / max(k_n, 1)
+    gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_gate_up.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+
+    rec = {
+        "metric": "emitted speech tokens/sec/GPU (batch 1, K=4)", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(dt / steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "half_b_k4: 0.5B-shaped bf16 target (24 layers, d=896, 14q/2kv x64, FFN 4864, V=6564), "
+                               "4-layer draft, batch 1, prefix 1024, K=4, T=1", "beta": args.beta,
+                   "weights": "independent N(0,0.02) target and draft"},
+        "mean_accepted_per_cycle": round(float(n_acc.mean()), 3),
+        "emitted_per_cycle": round(emitted / steps, 3),
+        "verify_us": round(verify_ms * 1e3, 1),
+        "verify_algorithmic_GBps": round(verify_gbs, 1),
+        "verify_frac_hbm_peak": round(verify_gbs / HBM_PEAK_GBS, 4),
+        "draft_step_us": round(draft_ms * 1e3, 1),
+        "ar_step_us": round(ar_ms * 1e3, 1),
+        "ar_tokens_per_s": round(1e3 / ar_ms, 1),
+        "speedup_vs_same_gpu_ar": round(value / (1e3 / ar_ms), 3),
+        "roofline": {"bound": "hbm", "kernel": "k_gemm_bf16<gate/up + SwiGLU>", "achieved": round(gu_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": traffic, "launches_timed": k_n, "avg_us": round(gu_ms * 1e3, 2)},
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload -------------------------------------------
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(tshape, tw, dshape, dw, prefix, K, args.beta, wl)
+    print(json.dumps(rec))
+
+
+def cpu_baseline(tshape, tw, dshape, dw, prefix, K, beta, wl):
+    """The fp64 oracle as it stands: whole SSD cycles (K draft steps + verification) at prefix 1024.  The caches
+    are filled with seeded random keys/values instead of an oracle prefill (timing does not depend on them)."""
+    import numpy as np
+    from oracle import decoder as OD
+    from oracle import ssd as OS
+    rng = np.random.default_rng(7)
+    t, d = OD.Model(tshape, tw), OD.Model(dshape, dw)
+    L = len(prefix) - 1
+    cycles = 3
+    tc, dc = OD.Cache(tshape, L + 64), OD.Cache(dshape, L + 64)
+    for c in (tc, dc):
+        c.k[:, :L] = rng.standard_normal(c.k[:, :L].shape) * 0.5
+        c.v[:, :L] = rng.standard_normal(c.v[:, :L].shape) * 0.5
+        c.length = L
+    cfg = OS.sample_cfg(beta=beta, temperature=wl["temperature"], top_k=wl["top_k"], seed=wl["seeds"]["rng"])
+    dcfg = OS.sample_cfg(temperature=wl["temperature"], top_k=wl["top_k"], seed=wl["seeds"]["rng"] + 1)
+    OS.ssd_generate(t, d, tc.copy(), dc.copy(), int(prefix[-1]), K, cfg, dcfg, 1)      # warm-up cycle
+    t0 = time.perf_counter()
+    toks, ns = OS.ssd_generate(t, d, tc, dc, int(prefix[-1]), K, cfg, dcfg, 10 ** 9, max_cycles=cycles)
+    dt = time.perf_counter() - t0
+    emitted = sum(n + 1 for n in ns)
+    try:
+        import threadpoolctl
+        threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": round(emitted / dt, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{len(ns)} SSD cycles (K={K} draft steps + one verification each) at prefix {L}, fp64 numpy, "
+                      f"caches filled with random keys/values", "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    main()

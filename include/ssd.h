@@ -163,6 +163,15 @@ int ssd_kv_state(ssd_kv* kv, int seq, void* stream, int32_t* len, int32_t* n_pen
                  int32_t* n_owned, int32_t* block_table, int block_table_cap);
 int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, int32_t* n_free, int32_t* dev_error_flag);
 
+/* ---- measurement ---------------------------------------------------------------------------------------
+ * Between ssd_profile_begin(kind) and ssd_profile_end() every launch of the named kernel family is bracketed
+ * by a pair of HIP events on its stream (this perturbs the pipeline slightly, so it is meant for a pass of its
+ * own, not for the region whose throughput is reported).  ssd_profile_end synchronises and returns the summed
+ * kernel time in milliseconds and the number of launches.  Kinds: 0 QKV GEMM, 1 attention (chunks + combine),
+ * 2 output-projection GEMM, 3 gate/up GEMM + SwiGLU, 4 down GEMM, 5 head GEMM. */
+int ssd_profile_begin(int kind);
+int ssd_profile_end(double* total_ms, int* launches);
+
 const char* ssd_strerror(int code);
 const char* ssd_last_error(void);
 

@@ -51,14 +51,14 @@ def ar_generate(model, cache, pending, cfg, n_tokens, seq=0, step0=0):
     return out
 
 
-def ssd_generate(target, draft, tcache, dcache, pending, K, cfg, dcfg, n_tokens, seq=0):
+def ssd_generate(target, draft, tcache, dcache, pending, K, cfg, dcfg, n_tokens, seq=0, max_cycles=None):
     """Alg. 1: repeat {draft K tokens, verify in parallel, accept / resample / bonus} until n_tokens are
     emitted (L_acc grows by n+1 per cycle; the last cycle's surplus is cut).  Both caches hold the same
     prefix on entry.  Returns (tokens, list of n_accepted per cycle)."""
     out, ns = [], []
     dpend = [pending]
     step = 0
-    while len(out) < n_tokens:
+    while len(out) < n_tokens and (max_cycles is None or step < max_cycles):
         xs, pds = [], []
         for i in range(K):
             tok, pd = draft_step(draft, dcache, dpend, dcfg, uniform24(dcfg["seed"], seq, step, i))

@@ -10,7 +10,7 @@ EXPORTED_SYMBOLS = [
     "ssd_model_workspace_bytes", "ssd_model_create", "ssd_model_destroy", "ssd_kv_pool_bytes",
     "ssd_kv_workspace_bytes", "ssd_kv_create", "ssd_kv_destroy", "ssd_prefill", "ssd_draft_step", "ssd_verify",
     "ssd_kv_rollback", "ssd_kv_follow", "ssd_verify_from_probs", "ssd_warp_probs", "ssd_kv_state",
-    "ssd_kv_free_stack", "ssd_strerror", "ssd_last_error",
+    "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_strerror", "ssd_last_error",
 ]
 
 
@@ -71,6 +71,8 @@ def load_library():
         "ssd_kv_state": (i32, [vp, i32, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                C.POINTER(C.c_int32), C.POINTER(C.c_int32), i32]),
         "ssd_kv_free_stack": (i32, [vp, vp, C.POINTER(C.c_int32), i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+        "ssd_profile_begin": (i32, [i32]),
+        "ssd_profile_end": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_int)]),
         "ssd_strerror": (C.c_char_p, [i32]),
         "ssd_last_error": (C.c_char_p, []),
     }
@@ -95,8 +97,9 @@ def _ptr(t):
 
 
 def _dev_bytes(n, device):
-    """Device buffer of n bytes, 256-byte aligned (torch's caching allocator aligns to 512)."""
-    t = torch.empty(max(int(n), 256), dtype=torch.uint8, device=device)
+    """Device buffer of n bytes, 256-byte aligned (torch's caching allocator aligns to 512), filled with 0xFF:
+    a kernel that read a workspace entry nobody wrote would see NaN (floats) or -1 (ints), not stale data."""
+    t = torch.full((max(int(n), 256),), 0xFF, dtype=torch.uint8, device=device)
     assert t.data_ptr() % 256 == 0
     return t
 
@@ -142,8 +145,8 @@ class Model:
         self.device = device
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            load_library().ssd_model_destroy(self.handle)
+        if getattr(self, "handle", None) and _LIB is not None:
+            _LIB.ssd_model_destroy(self.handle)
             self.handle = None
 
 
@@ -173,8 +176,8 @@ class KVCache:
         self.handle = h
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            load_library().ssd_kv_destroy(self.handle)
+        if getattr(self, "handle", None) and _LIB is not None:
+            _LIB.ssd_kv_destroy(self.handle)
             self.handle = None
 
     def state(self, seq):
@@ -222,6 +225,10 @@ def ssd_verify(target, kv, n_seqs, draft_tokens, draft_probs, K, cfg, step_ctr, 
                    next_token=torch.empty(n_seqs, dtype=torch.int32, device=dev),
                    probs=torch.empty((n_seqs, K + 1, V), dtype=torch.float32, device=dev) if want_probs else None,
                    logits=torch.empty((n_seqs, K + 1, V), dtype=torch.float32, device=dev) if want_logits else None)
+    for name, dt in (("n_accepted", torch.int32), ("next_token", torch.int32), ("probs", torch.float32),
+                     ("logits", torch.float32)):
+        t = out.get(name)
+        assert t is None or (t.dtype == dt and t.is_cuda), f"out[{name!r}] must be a {dt} device tensor"
     pl = None
     if prefix_len is not None:
         pl = (C.c_int32 * n_seqs)(*[int(v) for v in prefix_len])
@@ -237,6 +244,7 @@ def ssd_verify(target, kv, n_seqs, draft_tokens, draft_probs, K, cfg, step_ctr, 
 def ssd_draft_step(draft, kv_d, n_seqs, cfg, step_ctr, draft_idx, token_out, token_stride, probs_out, probs_stride):
     """token_out: int32 device tensor (view) whose element b*token_stride receives sequence b's token;
     probs_out: fp32 device tensor (view) whose row at b*probs_stride receives pd."""
+    assert token_out.dtype == torch.int32 and (probs_out is None or probs_out.dtype == torch.float32)
     _check(load_library().ssd_draft_step(draft.handle, kv_d.handle, n_seqs, C.byref(cfg), int(step_ctr), draft_idx,
                                          _ptr(token_out), token_stride, _ptr(probs_out), probs_stride, _stream()))
 
@@ -246,6 +254,7 @@ def ssd_kv_rollback(kv, seq, new_len, pending_token):
 
 
 def ssd_kv_follow(kv_d, n_seqs, K, n_accepted, next_token, draft_tokens):
+    assert n_accepted.dtype == next_token.dtype == draft_tokens.dtype == torch.int32
     _check(load_library().ssd_kv_follow(kv_d.handle, n_seqs, K, _ptr(n_accepted), _ptr(next_token),
                                         _ptr(draft_tokens), _stream()))
 
@@ -258,8 +267,8 @@ def ssd_verify_from_probs(pt, pd, tokens, uniforms, beta):
     n = torch.empty(B, dtype=torch.int32, device=dev)
     nxt = torch.empty(B, dtype=torch.int32, device=dev)
     flags = torch.empty(B, dtype=torch.int32, device=dev)
-    for t in (pt, pd, tokens, uniforms):
-        assert t is None or t.is_contiguous()
+    for t, dt in ((pt, torch.float32), (pd, torch.float32), (tokens, torch.int32), (uniforms, torch.float32)):
+        assert t is None or (t.is_contiguous() and t.dtype == dt)
     _check(load_library().ssd_verify_from_probs(_ptr(pt), _ptr(pd if K else None), _ptr(tokens if K else None),
                                                 _ptr(uniforms), B, K, V, float(beta), _ptr(n), _ptr(nxt), _ptr(flags),
                                                 _stream()))
@@ -272,3 +281,17 @@ def ssd_warp_probs(logits, cfg):
     probs = torch.empty_like(logits)
     _check(load_library().ssd_warp_probs(_ptr(logits), rows, V, C.byref(cfg), _ptr(probs), _stream()))
     return probs
+
+
+PROFILE_KINDS = {"qkv": 0, "attention": 1, "o": 2, "gate_up": 3, "down": 4, "head": 5}
+
+
+def ssd_profile_begin(kind):
+    _check(load_library().ssd_profile_begin(PROFILE_KINDS[kind]))
+
+
+def ssd_profile_end():
+    """Returns (summed kernel milliseconds, launches)."""
+    ms, n = C.c_double(), C.c_int()
+    _check(load_library().ssd_profile_end(C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -117,7 +117,32 @@ __device__ __forceinline__ void gemm_reduce_tile(const GemmArgs& g, float (*red)
 }
 
 // --------------------------------------------------------------------------------------- bf16 / MFMA
-// grid.x = work items (tile pairs x global splits).  MT = 16-row tiles of M.
+// Activations are kept in fp32 and fed to the matrix core as a sum of two bf16 values, x = hi + lo with
+// hi = the upper 16 bits of x and lo = bf16(x - hi): two MFMAs per weight fragment instead of one, which
+// the weight-streaming regime does not notice, and activation rounding (2^-17 instead of 2^-9 relative)
+// stops being the largest error of the bf16 path.  Weights are bf16 as stored.
+struct SplitA {
+  bf16x8 hi, lo;
+};
+__device__ __forceinline__ SplitA split_bf16(const u32x4 a, const u32x4 b) {
+  const uint32_t x[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t u0 = x[2 * i], u1 = x[2 * i + 1];
+    const uint32_t h0 = u0 & 0xFFFF0000u, h1 = u1 & 0xFFFF0000u;
+    const float r0 = __uint_as_float(u0) - __uint_as_float(h0);       // exact
+    const float r1 = __uint_as_float(u1) - __uint_as_float(h1);
+    h[i] = (h0 >> 16) | h1;
+    l[i] = (uint32_t)f_to_bf16(r0) | ((uint32_t)f_to_bf16(r1) << 16);
+  }
+  SplitA s;
+  s.hi = __builtin_bit_cast(bf16x8, u32x4{h[0], h[1], h[2], h[3]});
+  s.lo = __builtin_bit_cast(bf16x8, u32x4{l[0], l[1], l[2], l[3]});
+  return s;
+}
+
+// grid.x = work items (tile pairs x global splits).  MT = 16-row tiles of M.  A is fp32 [M][lda].
 template <int MT, int EPI, typename KVT>
 __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
   __shared__ float red[4][2][256];
@@ -135,7 +160,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
 
   const u32x4* w0 = (const u32x4*)g.W0 + (size_t)t0 * KT * 64 + lane;
   const u32x4* w1 = (const u32x4*)g.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
-  const bf16_t* A = (const bf16_t*)g.A;
+  const float* A = (const float*)g.A;
   const int arow = lane & 15, akoff = (lane >> 4) * 8;
 
   f32x4 acc[MT][2];
@@ -154,31 +179,45 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int row = mt * 16 + arow;
-      u32x4 a[U];
+      u32x4 a[U][2];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        a[u] = u32x4{0u, 0u, 0u, 0u};
-        if (row < g.M) a[u] = *(const u32x4*)(A + (size_t)row * g.lda + (kt + u) * 32 + akoff);
+        a[u][0] = u32x4{0u, 0u, 0u, 0u};
+        a[u][1] = u32x4{0u, 0u, 0u, 0u};
+        if (row < g.M) {
+          const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + (kt + u) * 32 + akoff);
+          a[u][0] = ap[0];
+          a[u][1] = ap[1];
+        }
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const bf16x8 av = __builtin_bit_cast(bf16x8, a[u]);
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b0[u]), acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b1[u]), acc[mt][1], 0, 0, 0);
+        const SplitA av = split_bf16(a[u][0], a[u][1]);
+        const bf16x8 bv0 = __builtin_bit_cast(bf16x8, b0[u]), bv1 = __builtin_bit_cast(bf16x8, b1[u]);
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.lo, bv0, acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.lo, bv1, acc[mt][1], 0, 0, 0);
+        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.hi, bv0, acc[mt][0], 0, 0, 0);
+        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.hi, bv1, acc[mt][1], 0, 0, 0);
       }
     }
   }
   for (; kt < ke; ++kt) {
-    const u32x4 b0 = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
-    const u32x4 b1 = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+    const bf16x8 bv0 = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(w0 + (size_t)kt * 64));
+    const bf16x8 bv1 = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(w1 + (size_t)kt * 64));
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int row = mt * 16 + arow;
-      u32x4 a = u32x4{0u, 0u, 0u, 0u};
-      if (row < g.M) a = *(const u32x4*)(A + (size_t)row * g.lda + kt * 32 + akoff);
-      const bf16x8 av = __builtin_bit_cast(bf16x8, a);
-      acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b0), acc[mt][0], 0, 0, 0);
-      acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b1), acc[mt][1], 0, 0, 0);
+      u32x4 a0 = u32x4{0u, 0u, 0u, 0u}, a1 = u32x4{0u, 0u, 0u, 0u};
+      if (row < g.M) {
+        const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + kt * 32 + akoff);
+        a0 = ap[0];
+        a1 = ap[1];
+      }
+      const SplitA av = split_bf16(a0, a1);
+      acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.lo, bv0, acc[mt][0], 0, 0, 0);
+      acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.lo, bv1, acc[mt][1], 0, 0, 0);
+      acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.hi, bv0, acc[mt][0], 0, 0, 0);
+      acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av.hi, bv1, acc[mt][1], 0, 0, 0);
     }
   }
   // accumulator register r of lane l is element (row 4*(l/16)+r, col l%16) of the 16x16 tile
@@ -193,7 +232,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
         red[wave][1][obase + r * 16] = acc[mt][1][r];
       }
       __syncthreads();
-      gemm_reduce_tile<EPI, BF16, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt);
+      gemm_reduce_tile<EPI, F32, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt);
     }
   }
 }

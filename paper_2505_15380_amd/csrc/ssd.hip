@@ -49,6 +49,52 @@ extern "C" const char* ssd_strerror(int code) {
 }
 extern "C" const char* ssd_last_error(void) { return g_err.c_str(); }
 
+// ------------------------------------------------------------------------------------------------ profiling
+static int g_prof_kind = -1;
+static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_events;
+struct ProfScope {                   // brackets the launches of one kernel family with a pair of events
+  hipEvent_t stop = nullptr;
+  hipStream_t st;
+  ProfScope(int kind, hipStream_t s) : st(s) {
+    if (kind != g_prof_kind) return;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    (void)hipEventRecord(a, st);
+    g_prof_events.emplace_back(a, b);
+    stop = b;
+  }
+  ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
+};
+enum { PROF_QKV = 0, PROF_ATTN = 1, PROF_O = 2, PROF_GATEUP = 3, PROF_DOWN = 4, PROF_HEAD = 5 };
+
+extern "C" int ssd_profile_begin(int kind) {
+  if (kind < 0 || kind > 5) return fail(SSD_EINVAL, "profile kind %d out of range", kind);
+  if (g_prof_kind >= 0) return fail(SSD_EINVAL, "a profile is already running");
+  g_prof_kind = kind;
+  return SSD_OK;
+}
+extern "C" int ssd_profile_end(double* total_ms, int* launches) {
+  if (g_prof_kind < 0) return fail(SSD_EINVAL, "no profile is running");
+  g_prof_kind = -1;
+  double sum = 0;
+  int n = 0;
+  int rc = SSD_OK;
+  for (auto& ev : g_prof_events) {
+    float ms = 0;
+    hipError_t e = hipEventSynchronize(ev.second);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
+    if (e != hipSuccess) rc = fail(SSD_EHIP, "profile events: %s", hipGetErrorString(e));
+    else { sum += ms; ++n; }
+    (void)hipEventDestroy(ev.first);
+    (void)hipEventDestroy(ev.second);
+  }
+  g_prof_events.clear();
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = n;
+  return rc;
+}
+
 // ------------------------------------------------------------------------------------------------ carving
 struct Carver {
   char* base;
@@ -227,7 +273,6 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   Carver cv(base);
   const int Mmax = max_seqs * max_rows;
   const int NC = cdiv(m->max_positions, ATT_CHUNK);
-  const size_t es = m->esize();
   const int nqd = c.n_q_heads * c.head_dim;
   int32_t* len = cv.take<int32_t>(max_seqs);
   int32_t* n_pend = cv.take<int32_t>(max_seqs);
@@ -240,13 +285,13 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   int32_t* ract = cv.take<int32_t>(Mmax);
   int32_t* scratch_i = cv.take<int32_t>(2 * max_seqs);
   float* h = cv.take<float>((size_t)Mmax * c.d_model);
-  void* xn = cv.take<char>((size_t)Mmax * c.d_model * es);
+  void* xn = cv.take<float>((size_t)Mmax * c.d_model);
   float* q = cv.take<float>((size_t)Mmax * nqd);
   float* o_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * c.head_dim);
   float* ml_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * 2);
-  void* attn = cv.take<char>((size_t)Mmax * nqd * es);
+  void* attn = cv.take<float>((size_t)Mmax * nqd);
   float* part = cv.take<float>((size_t)MAX_SPLITS * Mmax * c.d_model);
-  void* act = cv.take<char>((size_t)Mmax * c.d_ffn * es);
+  void* act = cv.take<float>((size_t)Mmax * c.d_ffn);
   float* logits = cv.take<float>((size_t)Mmax * c.vocab);
   float* probs = cv.take<float>((size_t)Mmax * c.vocab);
   if (kv) {
@@ -377,7 +422,7 @@ template <typename DT, int HD>
 static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, hipStream_t st) {
   hipLaunchKernelGGL((k_attn_chunk<HD, DT>), dim3(nchunks, nkv, B), dim3(BLOCK), 0, st, a);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_attn_combine<HD, DT>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
+  hipLaunchKernelGGL((k_attn_combine<HD, F32>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -414,48 +459,56 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   int rc;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& L = m->layers[l];
-    hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride, L.ln1,
+    hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride, L.ln1,
                        c.rms_eps, kv->xn, d);
     LAUNCH_CHECK();
     GemmArgs g = g0;                                       // QKV + bias + rotary + cache write
     g.A = kv->xn; g.lda = d; g.W0 = L.wqkv; g.W1 = L.wqkv; g.N = nqkv; g.K = d; g.gs = 1;
     g.bias = L.bqkv; g.q = kv->q; g.layer = l;
-    if ((rc = launch_gemm<DT, EPI_QKV>(m, g, (nq + 2 * nkv) * (hd / 32), st))) return rc;
+    { ProfScope ps(PROF_QKV, st); rc = launch_gemm<DT, EPI_QKV>(m, g, (nq + 2 * nkv) * (hd / 32), st); }
+    if (rc) return rc;
 
     AttnArgs a;
     a.q = kv->q; a.kv = kv->v; a.rows = rows; a.layer = l; a.nq = nq; a.scale = 1.0f / sqrtf((float)hd);
     a.o_part = kv->o_part; a.ml_part = kv->ml_part; a.NC = kv->NC; a.out = kv->attn;
-    if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, st);
-    else if (hd == 64) rc = launch_attn<DT, 64>(a, nchunks, nkv, B, M, st);
-    else rc = launch_attn<DT, 128>(a, nchunks, nkv, B, M, st);
+    {
+      ProfScope ps(PROF_ATTN, st);
+      if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, st);
+      else if (hd == 64) rc = launch_attn<DT, 64>(a, nchunks, nkv, B, M, st);
+      else rc = launch_attn<DT, 128>(a, nchunks, nkv, B, M, st);
+    }
     if (rc) return rc;
 
     g = g0;                                                // output projection -> k-split partials
     g.A = kv->attn; g.lda = nqd; g.W0 = L.wo; g.W1 = L.wo; g.N = d; g.K = nqd; g.gs = gs_o;
     g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
-    if ((rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_o, st))) return rc;
+    { ProfScope ps(PROF_O, st); rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_o, st); }
+    if (rc) return rc;
 
-    hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, gs_o, part_stride, L.ln2,
+    hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, gs_o, part_stride, L.ln2,
                        c.rms_eps, kv->xn, d);
     LAUNCH_CHECK();
 
     g = g0;                                                // gate / up + SwiGLU
     g.A = kv->xn; g.lda = d; g.W0 = L.wgate; g.W1 = L.wup; g.N = c.d_ffn; g.K = d; g.gs = 1; g.act = kv->act;
-    if ((rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st))) return rc;
+    { ProfScope ps(PROF_GATEUP, st); rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st); }
+    if (rc) return rc;
 
     g = g0;                                                // down projection -> k-split partials
     g.A = kv->act; g.lda = c.d_ffn; g.W0 = L.wdown; g.W1 = L.wdown; g.N = d; g.K = c.d_ffn; g.gs = gs_d;
     g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
-    if ((rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st))) return rc;
+    { ProfScope ps(PROF_DOWN, st); rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st); }
+    if (rc) return rc;
     n_part = gs_d;
   }
   if (!with_head) return SSD_OK;
-  hipLaunchKernelGGL((k_add_norm<DT>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride,
+  hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride,
                      m->final_norm, c.rms_eps, kv->xn, d);
   LAUNCH_CHECK();
   GemmArgs g = g0;
   g.A = kv->xn; g.lda = d; g.W0 = m->head; g.W1 = m->head; g.N = c.vocab; g.K = d; g.gs = 1;
   g.out = kv->logits; g.out_split_stride = 0; g.ldo = c.vocab;
+  ProfScope ps(PROF_HEAD, st);
   return launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(c.vocab, 16), 2), st);
 }
 

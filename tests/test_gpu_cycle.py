@@ -1,0 +1,207 @@
+"""GPU tests of the pieces around the verification: draft steps and whole SSD cycles in lockstep with the
+oracle, batches with ragged lengths, rollback, pool exhaustion, and row-count invariance (greedy SSD ==
+greedy autoregressive decoding on the GPU itself)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2505_15380_amd as pkg
+    pkg.load_library()
+
+
+def make_session(workload, K, beta=0.0, greedy=False, n_prefix=40, steps=12, temperature=None, draft_is_target=False):
+    import paper_2505_15380_amd as ssd
+    wl = si.workload(workload)
+    ts, ds = si.model_shape(wl["target"]), si.model_shape(wl["draft"])
+    tw, dw = si.make_weights(ts, wl["seeds"]["target"]), si.make_weights(ds, wl["seeds"]["draft"])
+    if draft_is_target:
+        ds, dw = ts, tw
+    toks = si.make_prefix(ts, 5, n_prefix, wl["seeds"]["prefix"])
+    T = wl["temperature"] if temperature is None else temperature
+    cfg = dict(beta=beta, temperature=T, top_k=0, greedy=greedy, seed=77)
+    dcfg = dict(beta=0.0, temperature=T, top_k=0, greedy=greedy, seed=78)
+    max_pos = len(toks) + steps * (K + 1) + 40
+    sess = ssd.SSDSession(ts, tw, ds, dw, 1, K, max_pos, ssd.sample_config(**cfg), ssd.sample_config(**dcfg))
+    sess.prefill(0, torch.from_numpy(toks).cuda())
+    return sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos)
+
+
+@pytest.mark.parametrize("workload,tol", [("tiny", 1e-5), ("mini", 2e-2)])
+@pytest.mark.parametrize("beta", [0.0, 0.4])
+def test_ssd_cycles_in_lockstep_with_oracle(workload, tol, beta):
+    """Draft steps (Eq. 2-3) and verification (Eq. 4-6) over several cycles, including the two-token catch-up
+    after a fully accepted cycle.  Every draft distribution and target distribution is compared; every drawn
+    token and decision must equal the oracle's canonical rule applied to the GPU's own fp32 probabilities."""
+    import paper_2505_15380_amd as ssd
+    from oracle import decoder as OD, ssd as OS
+    from oracle.accept import sample_canonical, accept_canonical
+    from oracle.philox import uniform24
+    from oracle.warp import warp_probs
+    K, steps = 3, 10
+    sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos) = make_session(workload, K, beta=beta, steps=steps)
+    t, d = OD.Model(ts, tw), OD.Model(ds, dw)
+    tc, dc = OD.Cache(ts, max_pos), OD.Cache(ds, max_pos)
+    OD.prefill(t, tc, toks[:-1]); OD.prefill(d, dc, toks[:-1])
+    pending, dpend = int(toks[-1]), [int(toks[-1])]
+    V = ts["vocab"]
+    seen_full = seen_reject = False
+    for step in range(steps):
+        # alternate a flat and a sharp temperature so that full acceptance and rejection both occur
+        cfg["temperature"] = dcfg["temperature"] = 1.0 if step % 2 == 0 else 0.05
+        sess.cfg, sess.dcfg = ssd.sample_config(**cfg), ssd.sample_config(**dcfg)
+        out = dict(n_accepted=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                   next_token=torch.zeros(1, dtype=torch.int32, device="cuda"),
+                   probs=torch.zeros((1, K + 1, V), dtype=torch.float32, device="cuda"), logits=None)
+        sess.cycle(step, out=out)
+        torch.cuda.synchronize()
+        gx, gpd = sess.x.cpu().numpy()[0], sess.pd.cpu().numpy()[0]
+        # oracle draft steps, teacher-forced with the GPU's tokens
+        for i in range(K):
+            lg = OD.forward_rows(d, dc, dpend)
+            dc.length += len(dpend)
+            ref = warp_probs(lg[-1:], dcfg["temperature"])[0]
+            assert np.abs(gpd[i] - ref).max() <= tol, (step, i)
+            tok = sample_canonical(gpd[i], uniform24(dcfg["seed"], 0, step, i))
+            assert tok == int(gx[i]), (step, i)
+            dpend = [tok]
+        r, u = OS.verify_uniforms(cfg["seed"], 0, step, K)
+        L = tc.length
+        gp = out["probs"].cpu().numpy()[0]
+        res = OS.verify_step(t, tc, pending, list(gx), gpd, OS.sample_cfg(**cfg), r, u, pt32=gp)
+        assert np.abs(gp - res["pt"]).max() <= tol
+        assert (int(out["n_accepted"][0]), int(out["next_token"][0])) == (res["n"], res["next"])
+        n, pending = res["n"], res["next"]
+        if n < K:
+            dc.length = L + 1 + n; dpend = [pending]; seen_reject = True
+        else:
+            dpend = [int(gx[-1]), pending]; seen_full = True
+        st, sd = sess.kv.state(0), sess.kv_d.state(0)
+        assert st["len"] == tc.length and st["pending"] == [pending]
+        assert sd["len"] == dc.length and sd["pending"] == dpend
+    assert seen_reject and seen_full
+
+
+@pytest.mark.parametrize("workload", ["tiny", "mini"])
+def test_greedy_ssd_equals_greedy_ar_on_gpu(workload):
+    """beta = 0, greedy: the SSD output is the target's own greedy continuation token for token; on the GPU this
+    also requires that a row verified among K+1 rows has the bits it has when decoded alone."""
+    K, n_tok = 4, 24
+    sess, _ = make_session(workload, K, greedy=True, steps=n_tok + 4)
+    ar = []
+    for s in range(n_tok):
+        out = sess.ar_step(s)
+        ar.append(int(out["next_token"][0]))
+    sess2, _ = make_session(workload, K, greedy=True, steps=n_tok + 4)
+    got = []
+    step = 0
+    while len(got) < n_tok:
+        out = sess2.cycle(step)
+        torch.cuda.synchronize()
+        n = int(out["n_accepted"][0])
+        got += [int(v) for v in sess2.x[0, :n]] + [int(out["next_token"][0])]
+        step += 1
+    assert got[:n_tok] == ar
+    assert len(set(ar)) > 2
+
+
+def test_draft_equal_to_target_accepts_everything():
+    K = 4
+    sess, _ = make_session("mini", K, beta=0.0, draft_is_target=True, steps=8)
+    for step in range(6):
+        out = sess.cycle(step)
+        assert int(out["n_accepted"][0]) == K
+    assert sess.kv.state(0)["len"] == sess.kv_d.state(0)["len"] + 1      # the draft owes x_K
+
+
+@pytest.mark.parametrize("workload,tol", [("tiny", 1e-5), ("mini", 2e-2)])
+def test_batched_ragged_verify_parity(workload, tol):
+    """Several sequences of different lengths in one call; per-sequence accept counts differ, blocks are shared
+    from one pool (block size 16), and the allocator state must follow the model exactly."""
+    from tests.parity import Pair, verify_parity_step
+    wl = si.workload(workload)
+    shape = si.model_shape(wl["target"])
+    B, K, steps = 3, 4, 5
+    lens = [23, 70, 49]
+    pair = Pair(wl["target"], wl["seeds"]["target"], 70 + steps * (K + 1) + 20, max_seqs=B, max_rows=8,
+                n_blocks=3 * 8 + 2, block_tokens=16)
+    for b in range(B):
+        pair.prefill(b, si.make_prefix(shape, 3, lens[b] - 3, 900 + b))
+    for b in range(B):
+        pair.check_state(b, tol)
+    pair.check_free_stack()
+    rng = np.random.default_rng(5)
+    cfg = dict(beta=0.1, temperature=1.0, top_k=0, greedy=False, seed=4321)
+    ns = []
+    for s in range(steps):
+        res = verify_parity_step(pair, cfg, K, s, rng, tol, tol, seqs=tuple(range(B)))
+        ns.append([r["n"] for r in res])
+        for b in range(B):
+            pair.check_state(b, tol, layers=[shape["n_layers"] - 1])
+        pair.check_free_stack()
+    assert len({tuple(n) for n in ns}) > 1 and any(len(set(n)) > 1 for n in ns)
+
+
+def test_rollback_and_reverify():
+    """After a verification that rejected drafts, positions below the new length are untouched, stale positions
+    are overwritten by the next call, and an explicit rollback frees whole blocks in the documented order."""
+    import paper_2505_15380_amd as ssd
+    from tests.parity import Pair, verify_parity_step
+    pair = Pair("tiny", 100, 200, max_seqs=1, max_rows=16, n_blocks=13, block_tokens=16)
+    shape = pair.shape
+    pair.prefill(0, si.make_prefix(shape, 0, 60, 1))
+    rng = np.random.default_rng(2)
+    cfg = dict(beta=0.0, temperature=0.2, top_k=0, greedy=False, seed=9)       # sharp: mostly rejections
+    for s in range(4):
+        verify_parity_step(pair, cfg, 6, s, rng, 1e-5, 1e-5)
+        pair.check_state(0, 1e-5)
+    L = pair.ocache[0].length
+    k_before, _ = pair.kv.gather(0, 1, 40)
+    ssd.ssd_kv_rollback(pair.kv, 0, 20, 17)
+    pair.ocache[0].length = 20; pair.pending[0] = 17; pair.alloc.set_length(0, 20)
+    pair.check_state(0, 1e-5)
+    pair.check_free_stack()
+    k_after, _ = pair.kv.gather(0, 1, 20)
+    assert (k_after == k_before[:20]).all()
+    for s in range(4, 7):
+        verify_parity_step(pair, cfg, 6, s, rng, 1e-5, 1e-5)
+        pair.check_state(0, 1e-5)
+        pair.check_free_stack()
+    with pytest.raises(ssd.SSDError):
+        ssd.ssd_kv_rollback(pair.kv, 0, L + 100, 0)
+
+
+def test_errors_are_reported_not_faulted():
+    import paper_2505_15380_amd as ssd
+    from tests.parity import Pair
+    pair = Pair("tiny", 100, 64, max_seqs=1, max_rows=8, n_blocks=3, block_tokens=16)
+    shape = pair.shape
+    pair.prefill(0, si.make_prefix(shape, 0, 40, 1))            # 39 cached positions -> 3 blocks
+    V = shape["vocab"]
+    x = torch.zeros((1, 7), dtype=torch.int32, device="cuda")
+    pd = torch.full((1, 7, V), 1.0 / V, dtype=torch.float32, device="cuda")
+    cfg = ssd.sample_config()
+    with pytest.raises(ssd.SSDError) as e:                      # 39 + 8 rows need 3 blocks: fits; 39+8=47 <= 48
+        ssd.ssd_verify(pair.gmodel, pair.kv, 1, x, pd, 7, cfg, 0, prefix_len=[38])
+    assert e.value.code == -1                                   # wrong prefix_len
+    ssd.ssd_verify(pair.gmodel, pair.kv, 1, x, pd, 7, cfg, 0, prefix_len=[39])
+    with pytest.raises(ssd.SSDError) as e:                      # pool (3 blocks = 48 positions) cannot take 8 more
+        for s in range(1, 4):
+            ssd.ssd_verify(pair.gmodel, pair.kv, 1, x, pd, 7, cfg, s)
+    assert e.value.code == -2
+    free, err = pair.kv.free_stack()
+    assert err == 0                                             # refused on the host, the device never overflowed
+    with pytest.raises(ssd.SSDError):
+        ssd.ssd_verify(pair.gmodel, pair.kv, 1, torch.zeros((1, 9), dtype=torch.int32, device="cuda"),
+                       torch.full((1, 9, V), 1.0 / V, dtype=torch.float32, device="cuda"), 9, cfg, 0)          # K + 1 > max_rows
+    with pytest.raises(ssd.SSDError):
+        ssd.ssd_verify(pair.gmodel, pair.kv, 2, torch.zeros((2, 7), dtype=torch.int32, device="cuda"),
+                       torch.full((2, 7, V), 1.0 / V, dtype=torch.float32, device="cuda"), 7, cfg, 0)          # n_seqs > max_seqs

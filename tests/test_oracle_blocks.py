@@ -9,7 +9,7 @@ import synth_inputs as si
 from oracle import decoder as D
 from oracle.warp import warp_probs
 
-torch.set_default_dtype(torch.float64)
+F64 = torch.float64
 
 
 def test_rmsnorm_vs_torch():
@@ -66,9 +66,9 @@ def torch_full_sequence_logits(shape, w, tokens):
     t = {k: (None if v is None else torch.tensor(np.asarray(v, dtype=np.float64))) for k, v in w.items()}
     S = len(tokens)
     h = F.embedding(torch.tensor(np.asarray(tokens, dtype=np.int64)), t["embed"])
-    pos = torch.arange(S, dtype=torch.float64)
+    pos = torch.arange(S, dtype=F64)
     freqs = shape["rope_base"] ** (-torch.arange(hd // 2, dtype=torch.float64) / (hd // 2))
-    rot = torch.polar(torch.ones(S, hd // 2), pos[:, None] * freqs[None, :])       # [S, hd/2] complex
+    rot = torch.polar(torch.ones(S, hd // 2, dtype=F64), pos[:, None] * freqs[None, :])       # [S, hd/2] complex
 
     def rope(x):                                                                    # x [S, H, hd]
         z = torch.complex(x[..., : hd // 2], x[..., hd // 2:]) * rot[:, None, :]
@@ -139,7 +139,7 @@ def test_warp_vs_torch_softmax_topk():
     np.testing.assert_allclose(warp_probs(z, 0.8), F.softmax(torch.tensor(z) / 0.8, dim=-1).numpy(), atol=1e-15)
     p = warp_probs(z, 1.3, top_k=7)
     vals, idx = torch.topk(torch.tensor(z), 7, dim=-1)
-    ref = torch.zeros(4, 50).scatter(1, idx, F.softmax(vals / 1.3, dim=-1)).numpy()
+    ref = torch.zeros(4, 50, dtype=F64).scatter(1, idx, F.softmax(vals / 1.3, dim=-1)).numpy()
     np.testing.assert_allclose(p, ref, atol=1e-15)
     assert ((p > 0).sum(axis=1) == 7).all()
     np.testing.assert_allclose(p.sum(axis=1), 1.0, atol=1e-14)
