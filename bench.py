@@ -169,8 +169,8 @@ def cpu_baseline(tshape, tw, dshape, dw, prefix, K, beta, wl):
     rng = np.random.default_rng(7)
     t, d = OD.Model(tshape, tw), OD.Model(dshape, dw)
     L = len(prefix) - 1
-    cycles = 3
-    tc, dc = OD.Cache(tshape, L + 64), OD.Cache(dshape, L + 64)
+    cycles = 128
+    tc, dc = OD.Cache(tshape, L + cycles * (K + 1) + 8), OD.Cache(dshape, L + cycles * (K + 1) + 8)
     for c in (tc, dc):
         c.k[:, :L] = rng.standard_normal(c.k[:, :L].shape) * 0.5
         c.v[:, :L] = rng.standard_normal(c.v[:, :L].shape) * 0.5
