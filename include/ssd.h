@@ -88,8 +88,9 @@ int    ssd_model_create(const ssd_model_config* cfg, const void* const* dev_weig
 int    ssd_model_destroy(ssd_model* m);
 
 /* ---- KV cache + sequence state ----------------------------------------------------------------------
- * Pool layout (dtype elements): [layer][0=K,1=V][block][kv_head][token_in_block][head_dim]; keys are stored
- * after the rotary embedding.  `max_rows` bounds the rows of one forward per sequence (K+1 for verify, the
+ * Pool layout (dtype elements): keys [layer][0][block][kv_head][token_in_block][head_dim], stored after the
+ * rotary embedding; values [layer][1][block][kv_head][head_dim][token_in_block] (token-minor, the order the
+ * matrix-core attention reads them in).  The pool must hold finite values (e.g. zeros) when handed over.  `max_rows` bounds the rows of one forward per sequence (K+1 for verify, the
  * chunk of a prefill); max_seqs*max_rows <= 128.  `pending_cap` is 1 for a target cache and 2 for a draft
  * cache (a draft may owe two tokens after a fully accepted cycle).  Blocks are handed out lowest id first;
  * see ssd_kv_state for the exact bookkeeping.  dev_ws must hold ssd_kv_workspace_bytes(). */
@@ -158,7 +159,8 @@ int ssd_warp_probs(const float* dev_logits, int rows, int V, const ssd_sample_co
  * Bookkeeping contract: a forward that writes R rows makes each sequence (ascending) own
  * ceil((len+R)/block_tokens) blocks, popping the free stack; a commit or rollback to new_len pushes back the
  * blocks with table index >= ceil(new_len/block_tokens), highest index first.  `free_stack` is returned bottom
- * first (the last entry is popped next).  Any output pointer may be NULL. */
+ * first (the last entry is popped next).  dev_error_flag: bit 0 = the device allocator ran out of blocks, bit 1 = a
+ * grid barrier of the persistent kernel timed out (the cache is unusable afterwards).  Any output pointer may be NULL. */
 int ssd_kv_state(ssd_kv* kv, int seq, void* stream, int32_t* len, int32_t* n_pending, int32_t pending[2],
                  int32_t* n_owned, int32_t* block_table, int block_table_cap);
 int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, int32_t* n_free, int32_t* dev_error_flag);
@@ -168,9 +170,18 @@ int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, in
  * by a pair of HIP events on its stream (this perturbs the pipeline slightly, so it is meant for a pass of its
  * own, not for the region whose throughput is reported).  ssd_profile_end synchronises and returns the summed
  * kernel time in milliseconds and the number of launches.  Kinds: 0 QKV GEMM, 1 attention (chunks + combine),
- * 2 output-projection GEMM, 3 gate/up GEMM + SwiGLU, 4 down GEMM, 5 head GEMM. */
+ * 2 output-projection GEMM, 3 gate/up GEMM + SwiGLU, 4 down GEMM, 5 head GEMM, 6 the persistent whole-forward
+ * kernel (used instead of 0-5 when the shape allows it). */
 int ssd_profile_begin(int kind);
 int ssd_profile_end(double* total_ms, int* launches);
+
+/* Barrier trace of the persistent forward kernel: with enable != 0 every later forward on `kv` records, per
+ * workgroup and grid barrier, the 100 MHz wall clock at arrival and at release.  When `out` is non-NULL the
+ * samples of the last forward are copied out first (synchronises `stream`): rows of 512 entries per workgroup,
+ * out[wg*512 + 2*b] = arrival and out[wg*512 + 2*b+1] = release of barrier b for b < *n_samples / 2 (the rest of a
+ * row is reserved); *n_wgs workgroups; cap >= 512 * workgroups. */
+int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
+                       int* n_samples);
 
 const char* ssd_strerror(int code);
 const char* ssd_last_error(void);

@@ -10,7 +10,7 @@ EXPORTED_SYMBOLS = [
     "ssd_model_workspace_bytes", "ssd_model_create", "ssd_model_destroy", "ssd_kv_pool_bytes",
     "ssd_kv_workspace_bytes", "ssd_kv_create", "ssd_kv_destroy", "ssd_prefill", "ssd_draft_step", "ssd_verify",
     "ssd_kv_rollback", "ssd_kv_follow", "ssd_verify_from_probs", "ssd_warp_probs", "ssd_kv_state",
-    "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_strerror", "ssd_last_error",
+    "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_trace_barriers", "ssd_strerror", "ssd_last_error",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library():
         "ssd_kv_free_stack": (i32, [vp, vp, C.POINTER(C.c_int32), i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
         "ssd_profile_begin": (i32, [i32]),
         "ssd_profile_end": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_int)]),
+        "ssd_trace_barriers": (i32, [vp, i32, vp, C.POINTER(C.c_uint64), i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
         "ssd_strerror": (C.c_char_p, [i32]),
         "ssd_last_error": (C.c_char_p, []),
     }
@@ -164,7 +165,7 @@ class KVCache:
         ws_bytes = lib.ssd_kv_workspace_bytes(model.handle, max_seqs, max_rows, n_blocks, max_blocks_per_seq)
         sh = model.shape
         dt = torch.bfloat16 if sh["dtype"] == "bf16" else torch.float32
-        # [layer][K/V][block][kv_head][token][head_dim]
+        # keys [layer][0][block][kv_head][token][head_dim]; values [layer][1][block][kv_head][head_dim][token]
         self.pool = torch.zeros((sh["n_layers"], 2, n_blocks, sh["n_kv_heads"], block_tokens, sh["head_dim"]),
                                 dtype=dt, device=model.device)
         assert self.pool.numel() * self.pool.element_size() == pool_bytes
@@ -202,10 +203,12 @@ class KVCache:
         (test helper: reads the pool through the block table)."""
         st = self.state(seq)
         bt = self.block_tokens
+        nkv, hd = self.model.shape["n_kv_heads"], self.model.shape["head_dim"]
         idx = torch.tensor([st["table"][p // bt] for p in range(length)], device=self.pool.device)
         off = torch.tensor([p % bt for p in range(length)], device=self.pool.device)
         k = self.pool[layer, 0, idx, :, off, :].float().cpu().numpy()
-        v = self.pool[layer, 1, idx, :, off, :].float().cpu().numpy()
+        vt = self.pool[layer, 1].reshape(self.n_blocks, nkv, hd, bt)          # values are stored [dim][token]
+        v = vt[idx, :, :, off].float().cpu().numpy()
         return k, v
 
 
@@ -283,7 +286,7 @@ def ssd_warp_probs(logits, cfg):
     return probs
 
 
-PROFILE_KINDS = {"qkv": 0, "attention": 1, "o": 2, "gate_up": 3, "down": 4, "head": 5}
+PROFILE_KINDS = {"qkv": 0, "attention": 1, "o": 2, "gate_up": 3, "down": 4, "head": 5, "persistent": 6}
 
 
 def ssd_profile_begin(kind):
@@ -295,3 +298,19 @@ def ssd_profile_end():
     ms, n = C.c_double(), C.c_int()
     _check(load_library().ssd_profile_end(C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def ssd_trace_barriers(kv, enable, read=False):
+    """Switch the persistent kernel's barrier trace on/off; with read=True return the last forward's samples as a
+    numpy array [workgroups, barriers, 2] of 100 MHz clock ticks (arrival, release)."""
+    lib = load_library()
+    if not read:
+        _check(lib.ssd_trace_barriers(kv.handle, int(enable), _stream(), None, 0, None, None))
+        return None
+    cap = 256 * 512
+    buf = (C.c_uint64 * cap)()
+    g, n = C.c_int(), C.c_int()
+    _check(lib.ssd_trace_barriers(kv.handle, int(enable), _stream(), buf, cap, C.byref(g), C.byref(n)))
+    raw = np.frombuffer(buf, dtype=np.uint64)[:g.value * 512].reshape(g.value, 512).copy()
+    kv._trace_raw = raw
+    return raw[:, :n.value].reshape(g.value, n.value // 2, 2)

@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(BLOCK) k_attn_chunk(AttnArgs a) {
       const int blk = a.kv.table[seq * a.kv.mbps + p / a.kv.bt];
       if (blk >= 0) {
         kx = KVT::ld(pool + kv_offset(a.kv, a.layer, 0, blk, kvh, p % a.kv.bt) + d);
-        vx = KVT::ld(pool + kv_offset(a.kv, a.layer, 1, blk, kvh, p % a.kv.bt) + d);
+        vx = KVT::ld(pool + kv_offset(a.kv, a.layer, 1, blk, kvh, 0) + d * a.kv.bt + p % a.kv.bt);
       }
     }
     Ks[c][d] = kx;

@@ -111,7 +111,8 @@ struct KvView {
   int n_layers, nkv, hd;
 };
 
-// Element offset of (layer, which(0=K,1=V), block, kv head, token in block, 0) in the pool.
+// Element offset of (layer, which(0=K,1=V), block, kv head, token in block, 0) in the pool.  Keys are stored
+// [token][dim]; values [dim][token], so for values only tok == 0 (the head's base) is meaningful here.
 __device__ __forceinline__ size_t kv_offset(const KvView& kv, int layer, int which, int blk, int head, int tok) {
   return ((((size_t)(layer * 2 + which) * kv.n_blocks + blk) * kv.nkv + head) * kv.bt + tok) * (size_t)kv.hd;
 }

@@ -80,9 +80,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int t0, int t1,
       const int seq = g.rows.seq0 + row / g.rows.R;
       const int blk = g.kv.table[seq * g.kv.mbps + pos / g.kv.bt];
       if (blk >= 0) {
-        typename KVT::T* dst = (typename KVT::T*)g.kv.pool + kv_offset(g.kv, g.layer, which, blk, kvh, pos % g.kv.bt) + d;
-        KVT::st(dst, v0);
-        KVT::st(dst + half, v1);
+        typename KVT::T* base = (typename KVT::T*)g.kv.pool + kv_offset(g.kv, g.layer, which, blk, kvh, 0);
+        const int tok = pos % g.kv.bt;
+        if (which == 0) {                                   // keys: [token][dim]
+          KVT::st(base + tok * hd + d, v0);
+          KVT::st(base + tok * hd + d + half, v1);
+        } else {                                            // values: [dim][token] (token-minor)
+          KVT::st(base + d * g.kv.bt + tok, v0);
+          KVT::st(base + (d + half) * g.kv.bt + tok, v1);
+        }
       }
     }
   }

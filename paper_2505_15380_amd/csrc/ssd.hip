@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -15,6 +16,7 @@
 #include "attention.h"
 #include "common.h"
 #include "gemm.h"
+#include "persistent.h"
 #include "sample.h"
 
 using namespace ssd;
@@ -66,10 +68,10 @@ struct ProfScope {                   // brackets the launches of one kernel fami
   }
   ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
 };
-enum { PROF_QKV = 0, PROF_ATTN = 1, PROF_O = 2, PROF_GATEUP = 3, PROF_DOWN = 4, PROF_HEAD = 5 };
+enum { PROF_QKV = 0, PROF_ATTN = 1, PROF_O = 2, PROF_GATEUP = 3, PROF_DOWN = 4, PROF_HEAD = 5, PROF_PERSISTENT = 6 };
 
 extern "C" int ssd_profile_begin(int kind) {
-  if (kind < 0 || kind > 5) return fail(SSD_EINVAL, "profile kind %d out of range", kind);
+  if (kind < 0 || kind > 6) return fail(SSD_EINVAL, "profile kind %d out of range", kind);
   if (g_prof_kind >= 0) return fail(SSD_EINVAL, "a profile is already running");
   g_prof_kind = kind;
   return SSD_OK;
@@ -125,6 +127,9 @@ struct ssd_model {
   const void* head;
   std::vector<LayerW> layers;
   const float2* rope;
+  PLayer* dev_layers;
+  std::vector<PLayer> host_layers;    // per-layer pointers; the persistent kernel needs them equally spaced
+  size_t layer_stride = 0;            // bytes between consecutive layers' tensors (0: not equally spaced)
   size_t esize() const { return c.dtype == SSD_DTYPE_BF16 ? 2 : 4; }
   int n_qkv() const { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 };
@@ -157,7 +162,8 @@ static size_t model_layout(const ssd_model_config& c, int max_positions, void* b
   const float* fn = cv.take<float>(d);
   const void* head = mat(c.vocab, d);
   const float2* rope = cv.take<float2>((size_t)max_positions * (c.head_dim / 2));
-  if (m) { m->embed = embed; m->final_norm = fn; m->head = head; m->rope = rope; m->layers.resize(c.n_layers); }
+  PLayer* dev_layers = cv.take<PLayer>(c.n_layers);
+  if (m) { m->embed = embed; m->final_norm = fn; m->head = head; m->rope = rope; m->dev_layers = dev_layers; m->layers.resize(c.n_layers); }
   for (int l = 0; l < c.n_layers; ++l) {
     LayerW w;
     w.ln1 = cv.take<float>(d);
@@ -239,6 +245,29 @@ extern "C" int ssd_model_create(const ssd_model_config* cfg, const void* const* 
     hipError_t e_ = hipGetLastError();
     if (e_ != hipSuccess) { delete m; return fail(SSD_EHIP, "rope table: %s", hipGetErrorString(e_)); }
   }
+  m->host_layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& L = m->layers[l];
+    m->host_layers[l] = PLayer{L.wqkv, L.wo, L.wgate, L.wup, L.wdown, L.ln1, L.ln2, L.bqkv};
+  }
+  m->layer_stride = 1;
+  if (c.n_layers > 1) {
+    const size_t st = (const char*)m->host_layers[1].wqkv - (const char*)m->host_layers[0].wqkv;
+    bool uniform = true;
+    for (int l = 1; l < c.n_layers; ++l) {
+      const PLayer &x = m->host_layers[l - 1], &y = m->host_layers[l];
+      auto gap = [&](const void* p, const void* q) { return (size_t)((const char*)q - (const char*)p); };
+      uniform = uniform && gap(x.wqkv, y.wqkv) == st && gap(x.wo, y.wo) == st && gap(x.wgate, y.wgate) == st &&
+                gap(x.wup, y.wup) == st && gap(x.wdown, y.wdown) == st && gap(x.ln1, y.ln1) == st && gap(x.ln2, y.ln2) == st &&
+                (!c.qkv_bias || gap(x.bqkv, y.bqkv) == st);
+    }
+    m->layer_stride = uniform ? st : 0;
+  }
+  {
+    hipError_t e_ = hipMemcpyAsync(m->dev_layers, m->host_layers.data(), sizeof(PLayer) * c.n_layers, hipMemcpyHostToDevice, st);
+    if (e_ == hipSuccess) e_ = hipStreamSynchronize(st);
+    if (e_ != hipSuccess) { delete m; return fail(SSD_EHIP, "layer table: %s", hipGetErrorString(e_)); }
+  }
 #undef COPY
 #undef TRY_RC
   *out = m;
@@ -263,6 +292,16 @@ struct ssd_kv {
   float *h, *q, *o_part, *ml_part, *part, *logits, *probs;
   void *xn, *attn, *act;
   int32_t* scratch_i;              // [2 * max_seqs]: n_accepted / next_token when the caller passes none
+  // persistent-kernel buffers (one instance per layer, see persistent.h)
+  float *p_h, *p_sumsq, *p_part, *p_att_o, *p_att_ml;
+  bf16_t *p_hg, *p_q, *p_attn, *p_act;        // split operand rows: 2 bf16 per value
+  int32_t* tickets;
+  uint32_t* bar;
+  unsigned long long* trace;       // [256][512] clock samples of the persistent kernel's barriers
+  bool trace_on = false;
+  int NP, p_rows;
+  uint32_t epoch = 0;
+  int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
   // host
   int32_t* mirror_host;
   std::vector<int> len_ub, npend_ub;
@@ -294,7 +333,25 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   void* act = cv.take<float>((size_t)Mmax * c.d_ffn);
   float* logits = cv.take<float>((size_t)Mmax * c.vocab);
   float* probs = cv.take<float>((size_t)Mmax * c.vocab);
+  const int NP = cdiv(m->max_positions, ATT_PART);
+  const bool p_ok = c.dtype == SSD_DTYPE_BF16 && c.head_dim == 64;
+  const int PR = p_ok ? std::min(Mmax, 16) : 0, L = c.n_layers;      // rows the persistent kernel can take
+  float* p_h = cv.take<float>((size_t)(2 * L + 1) * PR * c.d_model);
+  bf16_t* p_hg = cv.take<bf16_t>((size_t)(2 * L + 1) * PR * c.d_model * 2);
+  float* p_sumsq = cv.take<float>((size_t)(2 * L + 1) * PR * (c.d_model / 32 + 1));
+  bf16_t* p_q = cv.take<bf16_t>((size_t)L * PR * nqd * 2);
+  bf16_t* p_attn = cv.take<bf16_t>((size_t)L * PR * nqd * 2);
+  bf16_t* p_act = cv.take<bf16_t>((size_t)L * PR * c.d_ffn * 2);
+  float* p_part = cv.take<float>((size_t)2 * L * P_MAX_SPLITS * PR * c.d_model);
+  float* p_att_o = cv.take<float>((size_t)L * PR * c.n_q_heads * NP * 64);
+  float* p_att_ml = cv.take<float>((size_t)L * PR * c.n_q_heads * NP * 2);
+  int32_t* tickets = cv.take<int32_t>(std::max(c.d_model / 32 + 1, Mmax * c.n_kv_heads));
+  uint32_t* bar = cv.take<uint32_t>(128);
+  unsigned long long* trace = cv.take<unsigned long long>(p_ok ? 256 * 512 : 0);
   if (kv) {
+    kv->trace = trace;
+    kv->p_h = p_h; kv->p_hg = p_hg; kv->p_sumsq = p_sumsq; kv->p_q = p_q; kv->p_attn = p_attn; kv->p_act = p_act; kv->p_part = p_part; kv->p_att_o = p_att_o;
+    kv->p_att_ml = p_att_ml; kv->tickets = tickets; kv->bar = bar; kv->NP = NP; kv->p_rows = PR;
     kv->v.len = len; kv->v.n_pend = n_pend; kv->v.pend = pend; kv->v.owned = owned; kv->v.table = table;
     kv->v.free_stack = free_stack; kv->v.ctl = ctl;
     kv->rows.pos = rpos; kv->rows.active = ract;
@@ -350,6 +407,22 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   const int n = std::max(std::max(n_blocks, max_seqs * mbps), max_seqs);
   hipLaunchKernelGGL(k_kv_init, dim3(cdiv(n, 256)), dim3(256), 0, (hipStream_t)stream, v);
   e = hipGetLastError();
+  if (e == hipSuccess) e = hipMemsetAsync(kv->bar, 0, 128 * sizeof(uint32_t), (hipStream_t)stream);
+  if (e == hipSuccess)
+    e = hipMemsetAsync(kv->tickets, 0, sizeof(int32_t) * std::max(m->c.d_model / 32 + 1, max_seqs * max_rows * m->c.n_kv_heads),
+                       (hipStream_t)stream);
+  // The persistent forward needs: bf16 storage, head_dim 64, 16-token blocks, <= 16 query heads per kv head.
+  kv->persistent_wgs = 0;
+  if (e == hipSuccess && m->c.dtype == SSD_DTYPE_BF16 && m->c.head_dim == 64 && block_tokens == 16 && m->layer_stride &&
+      m->c.n_q_heads / m->c.n_kv_heads <= 16) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 16) {
+      int want = std::max(32, cdiv(m->c.d_ffn / 16, 2));            // two gate/up tile pairs per workgroup
+      if (const char* env = getenv("SSD_PERSISTENT_WGS")) want = atoi(env);
+      kv->persistent_wgs = std::max(0, std::min(want, cus));        // one workgroup per CU at most: all co-resident
+    }
+  }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
   return SSD_OK;
@@ -427,6 +500,42 @@ static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, hipStream
   return SSD_OK;
 }
 
+// The same forward as one persistent kernel (see persistent.h).
+static int forward_persistent(const ssd_model* m, ssd_kv* kv, Rows rows, int B, int pcap, const int32_t* dev_tokens,
+                              int tok_stride, bool with_head, hipStream_t st) {
+  const ssd_model_config& c = m->c;
+  PArgs a;
+  memset(&a, 0, sizeof a);
+  a.n_layers = c.n_layers; a.d = c.d_model; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.ffn = c.d_ffn; a.vocab = c.vocab;
+  a.n_embed = c.n_embed; a.eps = c.rms_eps; a.scale = 1.0f / sqrtf((float)c.head_dim);
+  a.embed = (const bf16_t*)m->embed; a.final_norm = m->final_norm; a.head = m->head; a.rope = m->rope;
+  a.layer0 = m->host_layers[0];
+  a.layer_stride = m->layer_stride;
+  a.kv = kv->v; a.rows = rows; a.pcap = pcap; a.n_seqs = B; a.tok_stride = tok_stride; a.with_head = with_head ? 1 : 0;
+  a.tokens = dev_tokens;
+  const size_t PR = kv->p_rows;
+  a.h = kv->p_h; a.hg = kv->p_hg; a.sumsq = kv->p_sumsq; a.q = kv->p_q; a.attn = kv->p_attn; a.act = kv->p_act;
+  a.part = kv->p_part; a.att_o = kv->p_att_o; a.att_ml = kv->p_att_ml; a.logits = kv->logits; a.NP = kv->NP;
+  a.st_h = PR * c.d_model; a.st_hg = 2 * PR * c.d_model; a.st_sq = PR * (c.d_model / 32);
+  a.st_q = 2 * PR * c.n_q_heads * c.head_dim; a.st_act = 2 * PR * c.d_ffn;
+  a.st_part = (size_t)P_MAX_SPLITS * PR * c.d_model; a.part_stride = PR * c.d_model;
+  a.st_att_o = PR * c.n_q_heads * kv->NP * 64; a.st_att_ml = PR * c.n_q_heads * kv->NP * 2;
+  int max_len = 0;
+  for (int s = rows.seq0; s < rows.seq0 + B; ++s) max_len = std::max(max_len, kv->len_ub[s]);
+  a.n_parts = std::min(kv->NP, cdiv(max_len + rows.R, ATT_PART));
+  a.tickets = kv->tickets; a.bar = kv->bar; a.epoch_base = kv->epoch;
+  a.trace = (kv->trace_on && 2 * (1 + 5 * c.n_layers) <= 512) ? kv->trace : nullptr;
+  const int G = kv->persistent_wgs, NU = 2 * G, npairs = c.d_model / 32;
+  auto splits = [&](int K) { return std::max(1, std::min(std::min(NU / npairs, (K / 32) / 4), P_MAX_SPLITS)); };
+  a.gs_o = (c.n_q_heads * c.head_dim) / 32 <= 4 * PF_K ? 1 : splits(c.n_q_heads * c.head_dim);   // <= PF_K k-tiles per wave: all prefetched
+  a.gs_d = splits(c.d_ffn);
+  kv->epoch += (with_head ? 1u : 0u) + 5u * (uint32_t)c.n_layers;      // barriers this launch executes
+  ProfScope ps(PROF_PERSISTENT, st);
+  hipLaunchKernelGGL(k_forward_persistent, dim3(G), dim3(PBLOCK), 0, st, a);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
 // One decoder forward for sequences [seq0, seq0+B), R rows each.  pcap = pending slots at the head of each
 // sequence's rows (0: all rows take explicit tokens).  Leaves logits [B*R][vocab] in the workspace when
 // with_head.  The caller has checked room.
@@ -438,6 +547,7 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   const int nqd = nq * hd, nqkv = m->n_qkv();
   Rows rows = kv->rows;
   rows.M = M; rows.R = R; rows.seq0 = seq0;
+  if (kv->persistent_wgs > 0 && M <= kv->p_rows) return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
 
   EmbedArgs e;
   e.kv = kv->v; e.rows = rows; e.pcap = pcap; e.n_seqs = B; e.tokens = dev_tokens; e.tok_stride = tok_stride;
@@ -739,10 +849,29 @@ extern "C" int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, 
   int32_t ctl[4];
   HIP_TRY(hipMemcpy(ctl, kv->v.ctl, sizeof ctl, hipMemcpyDeviceToHost));
   if (n_free) *n_free = ctl[0];
-  if (dev_error_flag) *dev_error_flag = ctl[1];
+  uint32_t bar_err = 0;
+  HIP_TRY(hipMemcpy(&bar_err, kv->bar + 64, 4, hipMemcpyDeviceToHost));
+  if (dev_error_flag) *dev_error_flag = ctl[1] | (bar_err ? 2 : 0);
   if (free_stack) {
     if (cap < ctl[0]) return fail(SSD_ENOMEM, "cap %d < %d free blocks", cap, ctl[0]);
     if (ctl[0]) HIP_TRY(hipMemcpy(free_stack, kv->v.free_stack, (size_t)ctl[0] * 4, hipMemcpyDeviceToHost));
   }
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ barrier trace
+extern "C" int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
+                                  int* n_samples) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  if (out) {
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    const int G = kv->persistent_wgs, S = 2 * (1 + 5 * kv->m->c.n_layers);
+    if (G <= 0 || S > 512) return fail(SSD_ENOSUP, "no persistent kernel trace for this cache");
+    if (cap < G * 512) return fail(SSD_ENOMEM, "cap %d < %d samples", cap, G * 512);
+    HIP_TRY(hipMemcpy(out, kv->trace, sizeof(unsigned long long) * 512 * G, hipMemcpyDeviceToHost));
+    if (n_wgs) *n_wgs = G;
+    if (n_samples) *n_samples = S;
+  }
+  kv->trace_on = enable != 0;
   return SSD_OK;
 }
