@@ -509,10 +509,11 @@ __device__ __forceinline__ void embed_phase(const PArgs& a) {
 // depend on the layer, so this is computed once per launch (after phase 0) and kept in registers.
 struct AttItem {
   int valid, m, kvh, part, pos, seq, old;     // old: every key of the wave's chunk was cached before this launch
-  int blk[4];
+  int koff[4];                                // per lane: element offset of its K fragment of key tile t in a layer's K plane
+  int voff[2];                                // per lane: element offset of its V fragment (dim tile 0) of k-step ks in a V plane
 };
 
-__device__ __forceinline__ AttItem att_item(const PArgs& a, int item, int uw) {
+__device__ __forceinline__ AttItem att_item(const PArgs& a, int item, int uw, int lane) {
   AttItem it;
   const int M = a.rows.M;
   it.valid = item < a.n_parts * a.nkv * M;
@@ -527,12 +528,20 @@ __device__ __forceinline__ AttItem att_item(const PArgs& a, int item, int uw) {
     it.valid = it.part * ATT_PART <= it.pos;
   }
   const int kbase = it.part * ATT_PART + uw * 64;
+  const int g = lane >> 4, c16 = lane & 15;
+  int blk[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int bi = (kbase >> 4) + t;
     const int b = (it.valid && bi < a.kv.mbps && bi * 16 <= it.pos)
                       ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.table + it.seq * a.kv.mbps + bi)) : -1;
-    it.blk[t] = b < 0 ? 0 : b;                                 // masked keys may read any valid block
+    blk[t] = b < 0 ? 0 : b;                                    // masked keys may read any valid block
+    it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];   // keys 32ks + 8g.. live in block 2ks + g/2
+    it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
   }
   it.old = it.valid && (kbase + 64 <= __builtin_amdgcn_readfirstlane(ld_state(a.kv.len + it.seq)));
   return it;
@@ -559,26 +568,23 @@ __device__ __forceinline__ void prefetch_kv(const PArgs& a, int layer, const Att
   }
 }
 
-// The 16 fragment loads of a wave's chunk.
+// The 16 fragment loads of a wave's chunk: a scalar plane base per layer plus the lane offsets of the item.
 __device__ __forceinline__ void load_kv(const PArgs& a, int layer, const AttItem& it, int lane, KVPre& kv) {
-  const int g = lane >> 4, c16 = lane & 15;
-  const bf16_t* pool = (const bf16_t*)a.kv.pool;
+  const size_t plane = (size_t)a.kv.n_blocks * a.kv.nkv * 1024;            // elements of one layer's K (or V) plane
+  const bf16_t* kp = (const bf16_t*)a.kv.pool + (size_t)(2 * layer) * plane;
+  const bf16_t* vp = kp + plane;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const bf16_t* kb_ = pool + kv_offset(a.kv, layer, 0, it.blk[t], it.kvh, c16) + g * 8;
-    kv.kf[t][0] = *(const u32x4*)kb_;
-    kv.kf[t][1] = *(const u32x4*)(kb_ + 32);
+    kv.kf[t][0] = *(const u32x4*)(kp + it.koff[t]);
+    kv.kf[t][1] = *(const u32x4*)(kp + it.koff[t] + 32);
   }
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int vblk = (g >> 1) ? it.blk[2 * ks + 1] : it.blk[2 * ks];       // keys 32ks + 8g.. live in block 2ks + g/2
-    const int tok0 = (g & 1) * 8;
+  for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-      kv.vf[ks][dt] = *(const u32x4*)(pool + kv_offset(a.kv, layer, 1, vblk, it.kvh, 0) + (16 * dt + c16) * 16 + tok0);
-  }
+    for (int dt = 0; dt < 4; ++dt) kv.vf[ks][dt] = *(const u32x4*)(vp + it.voff[ks] + dt * 256);
 }
 
+// ------------------------------------------------------------------------------------------------ attention phase
 // Item = (part of 256 keys, kv head, row m).  The G query heads of the row that share the kv head are the
 // 16-row tile (padded); wave w of the unit takes keys [256 part + 64 w, +64).  S = Q K^T and O = P V run on the
 // matrix cores with K fragments read straight from the cache rows and V fragments from the token-minor V layout.
@@ -601,7 +607,7 @@ __device__ __forceinline__ void attn_phase(const PArgs& a, int layer, const AttI
   float* att_ml = a.att_ml + (size_t)layer * a.st_att_ml;
   bf16_t* attn = a.attn + (size_t)layer * a.st_q;
   for (int rd = 0; rd < rounds; ++rd) {
-    const AttItem it = rd == 0 ? it0 : att_item(a, rd * NU + unit, uw);
+    const AttItem it = rd == 0 ? it0 : att_item(a, rd * NU + unit, uw, lane);
     const bool valid = it.valid;
     const int part = it.part, kvh = it.kvh, m = it.m, pos = it.pos;
     const int kbase = part * ATT_PART + uw * 64;             // first key of this wave's chunk
@@ -794,7 +800,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_persistent(PArgs a) {
   if (grid_barrier<2 * PF_K>(a, ++epoch, &sdead, [&]() { prefetch_weights<PE_QKV>(nx, pre); })) return;
   // every wave's round-0 attention item: rows and block table are final after phase 0
   const int wave_k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const AttItem ait = att_item(a, blockIdx.x * 2 + (wave_k >> 2), wave_k & 3);
+  const AttItem ait = att_item(a, blockIdx.x * 2 + (wave_k >> 2), wave_k & 3, threadIdx.x & 63);
   KVPre kvp;
   for (int l = 0; l < L; ++l) {
     gemm_phase<PE_QKV>(a, nx, pre, lds, sflag);

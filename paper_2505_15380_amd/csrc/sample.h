@@ -157,26 +157,37 @@ __global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
       idxmax = sh_idxmax;
     }
   }
-  const float invT_is_div = w.temperature;
+  // the row is read once into registers (all loads in flight together), then max / exp / sum / normalise
+  constexpr int PER = 64;                                   // V <= 16384
+  const float T = w.temperature;
+  float z[PER];
   float mx = -INFINITY;
-  for (int i = tid; i < V; i += BLOCK) {
-    const float v = x[i];
-    const uint32_t k = order_key(v);
-    const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
-    if (keep) mx = fmaxf(mx, v / invT_is_div);
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int i = tid + e * BLOCK;
+    z[e] = -INFINITY;
+    if (i < V) {
+      const float v = x[i];
+      const uint32_t k = order_key(v);
+      const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
+      if (keep) z[e] = v / T;
+    }
   }
+#pragma unroll
+  for (int e = 0; e < PER; ++e) mx = fmaxf(mx, z[e]);
   mx = block_max(mx, s4);
   float sum = 0.f;
-  for (int i = tid; i < V; i += BLOCK) {
-    const float v = x[i];
-    const uint32_t k = order_key(v);
-    const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
-    const float e = keep ? expf(v / invT_is_div - mx) : 0.f;
-    p[i] = e;
-    sum += e;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    z[e] = (z[e] == -INFINITY) ? 0.f : expf(z[e] - mx);
+    sum += z[e];
   }
   sum = block_sum(sum, s4);
-  for (int i = tid; i < V; i += BLOCK) p[i] = p[i] / sum;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int i = tid + e * BLOCK;
+    if (i < V) p[i] = z[e] / sum;
+  }
 }
 
 // ------------------------------------------------------------------------------ acceptance + resampling
@@ -241,17 +252,24 @@ __global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
   const float u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
   const float* prow = pt + (size_t)n * V;
   const float* drow = pd + (size_t)n * V;                   // only read when n < K
-  const int per = (V + BLOCK - 1) / BLOCK;                  // contiguous span of indices per thread
-  const int j0 = tid * per, j1 = min(j0 + per, V);
+  const int per = (V + BLOCK - 1) / BLOCK;                  // contiguous span of indices per thread (<= 64)
+  const int j0 = tid * per;
+  constexpr int PER = 64;
   int fallback = 0;
   bool residual = n < K;
   unsigned long long total;
+  float wgt[PER];
   for (;;) {
-    unsigned long long s = 0;
-    for (int j = j0; j < j1; ++j) {
-      const float wgt = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
-      s += fix40(wgt);
+    // the thread's span of weights, all loads in flight together
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int j = j0 + e;
+      wgt[e] = 0.f;
+      if (e < per && j < V) wgt[e] = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
     }
+    unsigned long long s = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) s += fix40(wgt[e]);
     part[tid] = s;
     const unsigned long long ws = wave_sum_u64(s);
     __syncthreads();
@@ -270,11 +288,12 @@ __global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
     for (int t = 0; t < tid; ++t) excl += part[t];
     if (excl <= tgt && tgt < excl + part[tid]) {
       unsigned long long c = excl;
-      int tok = j1 - 1;
-      for (int j = j0; j < j1; ++j) {
-        const float wgt = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
-        c += fix40(wgt);
-        if (c > tgt) { tok = j; break; }
+      int tok = min(j0 + per, V) - 1;
+      bool found = false;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        c += fix40(wgt[e]);
+        if (!found && c > tgt) { tok = j0 + e; found = true; }
       }
       sh_tok = tok;
     }

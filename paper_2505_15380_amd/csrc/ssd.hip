@@ -414,7 +414,8 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   // The persistent forward needs: bf16 storage, head_dim 64, 16-token blocks, <= 16 query heads per kv head.
   kv->persistent_wgs = 0;
   if (e == hipSuccess && m->c.dtype == SSD_DTYPE_BF16 && m->c.head_dim == 64 && block_tokens == 16 && m->layer_stride &&
-      m->c.n_q_heads / m->c.n_kv_heads <= 16) {
+      m->c.n_q_heads / m->c.n_kv_heads <= 16 &&
+      (size_t)n_blocks * m->c.n_kv_heads * 1024 < ((size_t)1 << 31)) {   // lane offsets into a K/V plane are 32-bit
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 16) {
