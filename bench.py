@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--beta", type=float, default=0.4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="after the benchmark, run a plain elementwise copy kernel over this many MiB (3 launches): the "
+                         "known-size reference that scales the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -161,6 +164,15 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
                      "traffic": traffic, "launches_timed": k_n, "avg_us": round(gu_ms * 1e3, 2)},
     }
+
+    if args.copy_calibration_mib > 0:               # reads N MiB and writes N MiB per launch, nothing else
+        n = args.copy_calibration_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        rec["copy_calibration_bytes_each_way"] = n * 4
 
     # ---- CPU oracle on a bounded sample of the same workload -------------------------------------------
     if not args.no_cpu_baseline:
