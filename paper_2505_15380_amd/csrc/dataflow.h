@@ -1,0 +1,977 @@
+// The decoder forward of one verification (Eq. 4) as one persistent kernel WITHOUT grid barriers between phases.
+//
+// Same decomposition as k_forward_persistent (five phases per layer, a unit of 4 waves per item, weights packed
+// as matrix-core fragments), but dependent phases are ordered by the data itself: everything a workgroup hands
+// to another workgroup is an 8-byte word {payload, tag}, stored with one agent-scope 64-bit store, where tag is
+// the number of this launch.  A consumer loads the words it needs with agent-scope 64-bit loads and repeats the
+// loads whose tag is not yet this launch's.  An aligned 8-byte store is observed whole, so a matching tag proves
+// the payload; no store has to be acknowledged before a flag is raised, no counter is shared, and the latency of a
+// dependency is one store plus one load instead of the five memory round trips of a barrier.
+//
+// Every word is written exactly once per launch (each layer and phase has its own buffers), and launches that use
+// the same cache workspace are ordered by the stream, so a tag can never be matched by an older value.
+//
+// Payloads: a GEMM operand value x is hi | lo << 16 with hi = upper 16 bits of x and lo = bf16(x - hi) (the two
+// bf16 whose sum the matrix core consumes); residual rows, sums of squares and partial results are fp32 bits;
+// new keys / values are bf16 bits.
+//
+// A workgroup stages the operand rows it needs in LDS once (all its waves poll in parallel, 12 words in flight per
+// thread), then feeds the matrix cores from LDS.  Weights of the following phase are requested as soon as the
+// operands of the current phase have arrived, so their HBM latency overlaps the current phase and the hand-over.
+//
+// Attention never reads this launch's new keys from the cache pool: the QKV phase stores them in the pool for
+// later launches and, tagged, in a side buffer; a wave whose 64-key chunk reaches the new positions patches its
+// key / value fragments from that buffer at the same fragment slots the pool would have supplied, so a row's bits
+// do not depend on how many rows are verified together.
+//
+// One grid barrier remains, after phase 0 (row bookkeeping and block reservation), once per launch.
+// All waits are bounded; a timeout raises the error flag and every workgroup leaves.
+#pragma once
+#include "persistent.h"
+
+namespace ssd {
+
+typedef unsigned long long u64;
+constexpr int DF_B = 12;                  // tagged words a thread keeps in flight while it stages operands
+constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
+constexpr int DF_ATT_ROWS = 64;           // query rows of one attention item: rows of a sequence x heads of a group
+constexpr int DF_NPF = 4;                 // attention parts merged per flight
+constexpr long DF_SPIN_LIMIT = 1L << 18;
+// LDS words: staging | sums of squares | unit reduction buffers, overlaid by the attention buffers of the two units
+constexpr int DF_SQ_WORDS = 1024;
+constexpr int DF_RED_WORDS = 2 * 2048;
+constexpr int DF_ATT_UNIT = 4096 + 512 + 512 + 4096 + 4096 + 128;      // Q | new K | new V | P | merge O | merge m,l
+constexpr int DF_LDS_WORDS = (DF_AW + DF_SQ_WORDS + DF_RED_WORDS) > 2 * DF_ATT_UNIT ? (DF_AW + DF_SQ_WORDS + DF_RED_WORDS)
+                                                                                  : 2 * DF_ATT_UNIT;
+
+struct DArgs {
+  int n_layers, d, nq, nkv, ffn, vocab, n_embed;
+  float eps, scale;
+  const bf16_t* embed;
+  const float* final_norm;
+  const void* head;
+  const float2* rope;
+  PLayer layer0;
+  size_t layer_stride;
+  KvView kv;
+  Rows rows;
+  int pcap, n_seqs, tok_stride, with_head;
+  const int32_t* tokens;
+  uint32_t tag;           // this launch's number: the upper half of every word written by it
+  u64* tw;                // base of the tagged workspace; the members below point into it
+  u64* h;                 // [2L+1][PR][d]      fp32: residual stream entering layer l at 2l, after attention at 2l+1
+  u64* hg;                // [2L+1][PR][d]      operand: h times the gain of the RMSNorm that consumes it
+  u64* sq;                // [2L+1][PR][d/32]   fp32: sums of squares of h over 32 columns
+  u64* q;                 // [L][PR][nq*64]     operand: rotated queries
+  u64* kvn;               // [L][PR][2][nkv*64] bf16: this launch's keys (rotated) and values
+  u64* attn;              // [L][PR][nq*64]     operand: attention output
+  u64* act;               // [L][PR][ffn]       operand: SwiGLU output
+  u64* part;              // [2L][P_MAX_SPLITS][PR][d] fp32: k-split partials (splits >= 1) of the output / down projections
+  u64* att_p;             // [L][PR][nq][NP][16][6] fp32: per part and 4-dim chunk: 4 weighted values, max, sum
+  float* logits;
+  size_t st_h, st_sq, st_q, st_kvn, st_act, st_part, st_att_p, part_stride;   // strides in words
+  int NP, n_parts, gs_o, gs_d;
+  uint32_t* bar;          // [0] arrivals, [32] flag, [64] error flag
+  unsigned long long* trace;
+};
+
+__device__ __forceinline__ u64 ld_word(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, AG); }
+__device__ __forceinline__ void st_word(u64* p, uint32_t payload, uint32_t tag) {
+  __hip_atomic_store(p, (u64)payload | ((u64)tag << 32), __ATOMIC_RELAXED, AG);
+}
+__device__ __forceinline__ void st_wordf(u64* p, float x, uint32_t tag) { st_word(p, __float_as_uint(x), tag); }
+__device__ __forceinline__ uint32_t split_payload(float x) {
+  const uint32_t u = __float_as_uint(x), h = u & 0xFFFF0000u;
+  return (h >> 16) | ((uint32_t)f_to_bf16(x - __uint_as_float(h)) << 16);
+}
+
+// Loads the words base[off[i]] (off == ~0: none) until every tag is this launch's.  False on a timeout.
+template <int N>
+__device__ __forceinline__ bool poll_words(const u64* base, const uint32_t (&off)[N], uint32_t tag, uint32_t (&out)[N],
+                                           uint32_t* err) {
+  u64 v[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = off[i] != 0xFFFFFFFFu ? ld_word(base + off[i]) : ((u64)tag << 32);
+  long spins = 0;
+  bool ok = true;
+  for (;;) {
+    bool all = true;
+#pragma unroll
+    for (int i = 0; i < N; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag);
+    if (all) break;
+    if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
+      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
+      ok = false;
+      break;
+    }
+    __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+      if ((uint32_t)(v[i] >> 32) != tag) v[i] = ld_word(base + off[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) out[i] = (uint32_t)v[i];
+  return ok;
+}
+
+// The 6 words of up to DF_NPF consecutive attention parts (96 words apart) of one 4-dim chunk.
+__device__ __forceinline__ bool poll_parts(const u64* base, uint32_t off0, int nparts, uint32_t tag, uint32_t (&out)[DF_NPF * 6],
+                                           uint32_t* err) {
+  u64 v[DF_NPF * 6];
+#pragma unroll
+  for (int i = 0; i < DF_NPF * 6; ++i) v[i] = (i / 6 < nparts) ? ld_word(base + off0 + (i / 6) * 96 + i % 6) : ((u64)tag << 32);
+  long spins = 0;
+  bool ok = true;
+  for (;;) {
+    bool all = true;
+#pragma unroll
+    for (int i = 0; i < DF_NPF * 6; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag);
+    if (all) break;
+    if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
+      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
+      ok = false;
+      break;
+    }
+    __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+    for (int i = 0; i < DF_NPF * 6; ++i)
+      if ((uint32_t)(v[i] >> 32) != tag) v[i] = ld_word(base + off0 + (i / 6) * 96 + i % 6);
+  }
+#pragma unroll
+  for (int i = 0; i < DF_NPF * 6; ++i) out[i] = (uint32_t)v[i];
+  return ok;
+}
+
+// ------------------------------------------------------------------------------------------------ GEMM phases
+struct DPhase {
+  const u64* A;           // operand rows [PR][K]
+  const u64* sq;          // [PR][K/32] sums of squares of the un-gained rows (nullptr: no RMSNorm)
+  const void* W0;
+  const void* W1;
+  int N, K, gs, items;
+  int shift;              // item i of round 0 runs on unit (i + shift) % units
+  int layer;
+  const float* bias;
+  const u64* h_in;        // PE_RESID
+  u64* h_out;
+  u64* hg_out;
+  u64* sq_out;
+  const float* gain_next;
+  u64* part;
+  u64* out;               // PE_QKV: q; PE_SWIGLU: act
+  u64* kvn;               // PE_QKV: side buffer of the new keys / values
+  float* logits;          // PE_LOGITS
+};
+
+// Operand words [k0, k0+kn) of rows [0, M) (row stride K words) -> As[row * (kn + 4) + k - k0], and the rows' sums of
+// squares [M][KT] -> sqs.  Thread gt of gn; the whole group polls in parallel.
+__device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, int k0, int kn, const u64* sq, int KT,
+                                              uint32_t* As, float* sqs, int gt, int gn) {
+  const int M = a.rows.M, nA = M * kn, total = nA + (sq ? M * KT : 0), stride = kn + 4;
+  const uint32_t a_off = (uint32_t)(A - a.tw), s_off = sq ? (uint32_t)(sq - a.tw) : 0u;
+  bool ok = true;
+  for (int base = 0; base < total; base += gn * DF_B) {
+    uint32_t off[DF_B], out[DF_B];
+#pragma unroll
+    for (int u = 0; u < DF_B; ++u) {
+      const int idx = base + u * gn + gt;
+      off[u] = 0xFFFFFFFFu;
+      if (idx < nA) {
+        const int row = idx / kn, k = idx - row * kn;
+        off[u] = a_off + (uint32_t)(row * K + k0 + k);
+      } else if (idx < total) {
+        off[u] = s_off + (uint32_t)(idx - nA);
+      }
+    }
+    ok = poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64) && ok;
+#pragma unroll
+    for (int u = 0; u < DF_B; ++u) {
+      const int idx = base + u * gn + gt;
+      if (idx < nA) {
+        const int row = idx / kn, k = idx - row * kn;
+        As[row * stride + k] = out[u];
+      } else if (idx < total) {
+        sqs[idx - nA] = __uint_as_float(out[u]);
+      }
+    }
+  }
+  return ok;
+}
+
+// hi / lo fragments (8 consecutive k each) of a lane from 8 staged payload words
+__device__ __forceinline__ void frag_from_lds(const uint32_t* p, u32x4& hi, u32x4& lo) {
+  const u32x4 w0 = *(const u32x4*)p, w1 = *(const u32x4*)(p + 4);
+  hi = u32x4{__builtin_amdgcn_perm(w0[1], w0[0], 0x05040100u), __builtin_amdgcn_perm(w0[3], w0[2], 0x05040100u),
+             __builtin_amdgcn_perm(w1[1], w1[0], 0x05040100u), __builtin_amdgcn_perm(w1[3], w1[2], 0x05040100u)};
+  lo = u32x4{__builtin_amdgcn_perm(w0[1], w0[0], 0x07060302u), __builtin_amdgcn_perm(w0[3], w0[2], 0x07060302u),
+             __builtin_amdgcn_perm(w1[1], w1[0], 0x07060302u), __builtin_amdgcn_perm(w1[3], w1[2], 0x07060302u)};
+}
+
+#ifdef SSD_TRACE_FINE
+#define DF_FINE(k) do { if (a.trace && threadIdx.x == 0 && ph.layer == 3) a.trace[(size_t)blockIdx.x * 512 + 256 + (((slot) - 2) % 10 / 2) * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define DF_FINE(k) do { } while (0)
+#endif
+#define DF_STAMP(slot) do { if (a.trace && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * 512 + (slot)] = wall_clock64(); } while (0)
+
+__device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU) {
+  int i = unit - shift;
+  return i < 0 ? i + NU : i;
+}
+
+// Weight fragments of the unit's round-0 item of phase `ph` (epilogue kind epi), as prefetch_weights does, with the
+// kind and the unit -> item shift taken at run time.  Does nothing when the unit has no item in that phase.
+__device__ __forceinline__ void df_prefetch(const DPhase& ph, int epi, WPre& pre) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int unit = blockIdx.x * 2 + (wave >> 2), NU = gridDim.x * 2;
+  const int item = df_item_of_unit(unit, ph.shift, NU);
+  if (item >= ph.items) return;
+  int t0, t1, split = 0;
+  if (epi == PE_QKV) { t0 = (item >> 1) * 4 + (item & 1); t1 = t0 + 2; }
+  else if (epi == PE_SWIGLU) { t0 = item; t1 = item; }
+  else {
+    const int npairs = (((ph.N + 15) >> 4) + 1) >> 1;
+    split = item / npairs;
+    const int p = item - split * npairs;
+    t0 = 2 * p; t1 = 2 * p + 1;
+  }
+  int kb, ke;
+  wave_krange(ph, split, wave & 3, kb, ke);
+  const int KT = ph.K >> 5, ntiles = (ph.N + 15) >> 4;
+  const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
+  const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(t1 < ntiles ? t1 : t0) * KT * 64 + lane;
+#pragma unroll
+  for (int u = 0; u < PF_K; ++u) {
+    const int kt = (kb + u < ke) ? kb + u : kb;
+    pre.b0[u] = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
+    pre.b1[u] = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+  }
+}
+
+// One GEMM phase; the caller skips it for a workgroup none of whose units has an item.  When `pre_ok`, `pre` holds the
+// weight fragments of the unit's round-0 item (requested one or more phases earlier).  `after` is called once the
+// products of round 0 are issued and `pre` is free again (for the unit that sums the splits: after its wait for them).
+// Returns true if the workgroup has to leave (timeout somewhere in the grid).
+template <int EPI, typename FAfter>
+__device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, const WPre& pre, bool pre_ok, uint32_t* lds,
+                                              const int* srow, int* sdead, int slot, FAfter&& after) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int usel = wave >> 2, uw = wave & 3, ut = tid & 255;
+  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  const int uitem = df_item_of_unit(unit, ph.shift, NU);
+  uint32_t* As = lds;
+  float* sqs = (float*)(lds + DF_AW);
+  float (*red)[2][256] = (float (*)[2][256])((float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048);
+  const int M = a.rows.M;
+  const int KT = ph.K >> 5, ntiles = (ph.N + 15) >> 4;
+  const int arow = lane & 15, g = lane >> 4;
+  const int row = ut >> 4, col = ut & 15;
+  const int rounds = (ph.items + NU - 1) / NU;
+  const bool shared = ph.gs == 1;                      // both units of the workgroup consume the same operand rows
+  for (int rd = 0; rd < rounds; ++rd) {
+    DF_FINE(0);
+    const int item = rd * NU + uitem;
+    int t0, t1, split, kb = 0, ke = 0;
+    const bool valid = gemm_item<EPI>(ph, item, t0, t1, split);
+    if (valid) wave_krange(ph, split, uw, kb, ke);
+    const bool has1 = t1 < ntiles;
+    const bool live = valid && row < M;
+    const bool reducer = EPI == PE_RESID && valid && split == 0;
+    const int n0 = t0 * 16 + col, n1 = t1 * 16 + col;
+    // the residual input of the unit that finishes the rows was written a phase or more ago: request it now
+    u64 hw0 = 0, hw1 = 0;
+    if (reducer && row < M) {
+      hw0 = ld_word(ph.h_in + (size_t)row * ph.N + n0);
+      hw1 = ld_word(ph.h_in + (size_t)row * ph.N + n1);
+    }
+    // ---- operands
+    int k0 = 0, kn = ph.K;
+    const uint32_t* Au = As;
+    bool ok = true;
+    if (shared) {
+      if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK);
+    } else {
+      const int per_s = KT / ph.gs, rem_s = KT - per_s * ph.gs;
+      k0 = (split * per_s + min(split, rem_s)) * 32;
+      kn = (per_s + (split < rem_s ? 1 : 0)) * 32;
+      Au = As + usel * (DF_AW / 2);
+      if (valid) ok = stage_operand(a, ph.A, ph.K, k0, kn, nullptr, 0, (uint32_t*)Au, sqs, ut, 256);
+    }
+    if (!ok) *sdead = 1;
+    __syncthreads();
+    if (*sdead) return true;
+    // ---- epilogue operands that do not depend on the product: requested before the weights of a later phase, so
+    //      that the epilogue never waits behind those (vector memory operations of a wave return in order)
+    float bias0 = 0.f, bias1 = 0.f, gn0 = 0.f, gn1 = 0.f;
+    float2 cs = float2{1.f, 0.f};
+    int pos = 0, active = 0, rblk = -1;
+    if (EPI == PE_QKV && live) {
+      if (ph.bias) { bias0 = ph.bias[n0]; bias1 = ph.bias[n0 + 32]; }
+      pos = srow[row]; active = srow[16 + row]; rblk = srow[32 + row];
+      cs = a.rope[(size_t)pos * 32 + (n0 & 63)];
+    }
+    if (EPI == PE_RESID && live) { gn0 = ph.gain_next[n0]; gn1 = ph.gain_next[n1]; }
+    if (rd == 0) DF_STAMP(slot);
+    DF_FINE(1);
+    // ---- products
+    f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
+    const int stride = kn + 4;
+    const uint32_t* arow_p = Au + arow * stride + g * 8 - k0;
+    if (valid) {
+      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
+      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
+      if (rd == 0 && pre_ok) {
+#pragma unroll
+        for (int u = 0; u < PF_K; ++u)
+          if (kb + u < ke) {
+            u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+            if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
+            mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
+          }
+      } else {
+#pragma unroll
+        for (int u = 0; u < PF_K; ++u)
+          if (kb + u < ke) {
+            u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+            if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
+            mfma_pair(xh, xl, __builtin_nontemporal_load(w0 + (size_t)(kb + u) * 64),
+                      __builtin_nontemporal_load(w1 + (size_t)(kb + u) * 64), acc0, acc1);
+          }
+      }
+      for (int kt = kb + PF_K; kt < ke; ++kt) {
+        u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+        if (arow < M) frag_from_lds(arow_p + kt * 32, xh, xl);
+        mfma_pair(xh, xl, __builtin_nontemporal_load(w0 + (size_t)kt * 64), __builtin_nontemporal_load(w1 + (size_t)kt * 64),
+                  acc0, acc1);
+      }
+    }
+    const int obase = (g * 4) * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      red[uw][0][obase + r * 16] = acc0[r];
+      red[uw][1][obase + r * 16] = acc1[r];
+    }
+#ifdef SSD_TRACE_FINE
+    if (acc0[0] == 123456.f) *sdead = 2;       // forces the products to be complete before the stamp
+#endif
+    DF_FINE(2);
+    float sq = 0.f;
+    if (ph.sq && row < M)
+      for (int p = col; p < KT; p += 16) sq += sqs[row * KT + p];
+    __syncthreads();
+    DF_FINE(4);
+    float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
+    float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
+    if (ph.sq) {
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+      const float inv = 1.0f / sqrtf(sq / (float)ph.K + a.eps);
+      v0 *= inv;
+      v1 *= inv;
+    }
+    if (EPI == PE_QKV) {
+      if (live) {
+        const int head = n0 >> 6, dd = n0 & 63;                      // dd < 32
+        v0 += bias0; v1 += bias1;
+        if (head < a.nq + a.nkv) {
+          const float r0 = v0 * cs.x - v1 * cs.y, r1 = v1 * cs.x + v0 * cs.y;
+          v0 = r0; v1 = r1;
+        }
+        if (head < a.nq) {
+          u64* qo = ph.out + (size_t)row * (a.nq * 64) + head * 64 + dd;
+          st_word(qo, split_payload(v0), a.tag);
+          st_word(qo + 32, split_payload(v1), a.tag);
+        } else {
+          const int which = head < a.nq + a.nkv ? 0 : 1;
+          const int kvh = head - a.nq - which * a.nkv;
+          const bf16_t b0 = f_to_bf16(v0), b1 = f_to_bf16(v1);
+          u64* ko = ph.kvn + ((size_t)row * 2 + which) * (a.nkv * 64) + kvh * 64 + dd;
+          st_word(ko, b0, a.tag);
+          st_word(ko + 32, b1, a.tag);
+          if (active && rblk >= 0) {
+            bf16_t* base = (bf16_t*)a.kv.pool + kv_offset(a.kv, ph.layer, which, rblk, kvh, 0);
+            const int tok = pos & 15;
+            if (which == 0) { st_ag(base + tok * 64 + dd, b0); st_ag(base + tok * 64 + dd + 32, b1); }
+            else { st_ag(base + dd * 16 + tok, b0); st_ag(base + (dd + 32) * 16 + tok, b1); }
+          }
+        }
+      }
+    } else if (EPI == PE_SWIGLU) {
+      if (live && n0 < ph.N) st_word(ph.out + (size_t)row * ph.N + n0, split_payload(v0 / (1.0f + expf(-v0)) * v1), a.tag);
+    } else if (EPI == PE_LOGITS) {
+      if (live) {
+        if (n0 < ph.N) ph.logits[(size_t)row * ph.N + n0] = v0;
+        if (has1 && n1 < ph.N) ph.logits[(size_t)row * ph.N + n1] = v1;
+      }
+    } else {  // PE_RESID: the unit of split 0 sums the splits in ascending order and adds the residual
+      const int pair = t0 >> 1;
+      if (valid && split != 0) {
+        if (row < M) {
+          u64* o = ph.part + (size_t)split * a.part_stride + (size_t)row * ph.N;
+          st_wordf(o + n0, v0, a.tag);
+          st_wordf(o + n1, v1, a.tag);
+        }
+      } else if (valid) {
+        float q2 = 0.f;
+        if (row < M) {
+          constexpr int NW = 2 * (P_MAX_SPLITS - 1) + 2;
+          uint32_t off[NW], out[NW];
+          const uint32_t p_off = (uint32_t)(ph.part - a.tw) + (uint32_t)(row * ph.N);
+#pragma unroll
+          for (int s = 1; s < P_MAX_SPLITS; ++s) {
+            const bool use = s < ph.gs;
+            off[2 * (s - 1)] = use ? p_off + (uint32_t)(s * a.part_stride) + n0 : 0xFFFFFFFFu;
+            off[2 * (s - 1) + 1] = use ? p_off + (uint32_t)(s * a.part_stride) + n1 : 0xFFFFFFFFu;
+          }
+          const uint32_t h_off = (uint32_t)(ph.h_in - a.tw) + (uint32_t)(row * ph.N);
+          const bool h_ok = (uint32_t)(hw0 >> 32) == a.tag && (uint32_t)(hw1 >> 32) == a.tag;
+          off[NW - 2] = h_ok ? 0xFFFFFFFFu : h_off + n0;
+          off[NW - 1] = h_ok ? 0xFFFFFFFFu : h_off + n1;
+          if (ph.gs > 1 || !h_ok) {
+            if (!poll_words<NW>(a.tw, off, a.tag, out, a.bar + 64)) *sdead = 1;
+          }
+          if (h_ok) { out[NW - 2] = (uint32_t)hw0; out[NW - 1] = (uint32_t)hw1; }
+#pragma unroll
+          for (int s = 1; s < P_MAX_SPLITS; ++s)
+            if (s < ph.gs) { v0 += __uint_as_float(out[2 * (s - 1)]); v1 += __uint_as_float(out[2 * (s - 1) + 1]); }
+          v0 += __uint_as_float(out[NW - 2]);
+          v1 += __uint_as_float(out[NW - 1]);
+          st_wordf(ph.h_out + (size_t)row * ph.N + n0, v0, a.tag);
+          st_wordf(ph.h_out + (size_t)row * ph.N + n1, v1, a.tag);
+          st_word(ph.hg_out + (size_t)row * ph.N + n0, split_payload(v0 * gn0), a.tag);
+          st_word(ph.hg_out + (size_t)row * ph.N + n1, split_payload(v1 * gn1), a.tag);
+          q2 = v0 * v0 + v1 * v1;
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) q2 += __shfl_xor(q2, o, WAVE);
+        if (col == 0 && row < M) st_wordf(ph.sq_out + (size_t)row * (ph.N >> 5) + pair, q2, a.tag);
+      }
+    }
+    if (rd == 0) DF_STAMP(slot + 1);
+    DF_FINE(5);
+    if (rd == 0) {                       // the stores of this phase are on their way: now the weights of a later phase
+      __builtin_amdgcn_sched_barrier(0);
+      after();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    DF_FINE(3);
+    __syncthreads();
+    if (*sdead) return true;
+    DF_FINE(6);
+  }
+  return false;
+}
+
+// ------------------------------------------------------------------------------------------------ phase 0
+// Rows, embedding, block reservation.  Item = row.
+__device__ __forceinline__ void df_embed_phase(const DArgs& a) {
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), usel = wave >> 2, ut = tid & 255;
+  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  const int M = a.rows.M, R = a.rows.R, d = a.d;
+  for (int m = unit; m < M; m += NU) {
+    const int brel = m / R, j = m - brel * R;
+    const int seq = a.rows.seq0 + brel;
+    const int npend = a.pcap ? ld_state(a.kv.n_pend + seq) : 0;
+    const int off = a.pcap - npend;
+    const int len = ld_state(a.kv.len + seq);
+    int tok, pos, active;
+    if (j < off) { tok = ld_state(a.kv.pend + seq * 2); pos = len; active = 0; }
+    else {
+      pos = len + (j - off); active = 1;
+      tok = j < a.pcap ? ld_state(a.kv.pend + seq * 2 + (j - off)) : ld_state(a.tokens + (size_t)brel * a.tok_stride + (j - a.pcap));
+    }
+    tok = min(max(tok, 0), a.n_embed - 1);
+    if (ut == 0) { st_ag(a.rows.pos + m, pos); st_ag(a.rows.active + m, active); }
+    const bf16_t* src = a.embed + (size_t)tok * d;
+    const float* gain = a.layer0.ln1;
+    for (int p = ut >> 5; p < (d >> 5); p += 8) {
+      const int c = p * 32 + (ut & 31);
+      const float v = bf16_to_f(src[c]);
+      st_wordf(a.h + (size_t)m * d + c, v, a.tag);
+      st_word(a.hg + (size_t)m * d + c, split_payload(v * gain[c]), a.tag);
+      float sq = v * v;
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+      if ((ut & 31) == 0) st_wordf(a.sq + (size_t)m * (d >> 5) + p, sq, a.tag);
+    }
+  }
+  if (blockIdx.x == 0 && tid == 0) {
+    int top = ld_state(a.kv.ctl);
+    for (int b = 0; b < a.n_seqs; ++b) {
+      const int s = a.rows.seq0 + b;
+      const int o = a.pcap ? a.pcap - ld_state(a.kv.n_pend + s) : 0;
+      const int need = ceil_div(ld_state(a.kv.len + s) + a.rows.R - o, a.kv.bt);
+      int own = ld_state(a.kv.owned + s);
+      while (own < need) {
+        if (top <= 0 || own >= a.kv.mbps) { a.kv.ctl[1] = 1; break; }
+        st_ag(a.kv.table + s * a.kv.mbps + own, ld_state(a.kv.free_stack + --top));
+        ++own;
+      }
+      a.kv.owned[s] = own;
+    }
+    a.kv.ctl[0] = top;
+  }
+}
+
+// The one grid barrier of a launch: arrive on a counter; the last arrival clears it and publishes the launch
+// number on a separate line that the others poll.  Bounded.
+__device__ __forceinline__ bool df_start_barrier(const DArgs& a, int* sdead) {
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int dead = 0;
+    if (__hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, AG) == gridDim.x - 1) {
+      __hip_atomic_store(a.bar, 0u, __ATOMIC_RELAXED, AG);
+      __builtin_amdgcn_s_waitcnt(0);
+      __hip_atomic_store(a.bar + 32, a.tag, __ATOMIC_RELAXED, AG);
+    } else {
+      long spins = 0;
+      while ((int32_t)(__hip_atomic_load(a.bar + 32, __ATOMIC_RELAXED, AG) - a.tag) < 0) {
+        if (++spins > (1L << 21) || __hip_atomic_load(a.bar + 64, __ATOMIC_RELAXED, AG) != 0) {
+          __hip_atomic_store(a.bar + 64, 1u, __ATOMIC_RELAXED, AG);
+          dead = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    *sdead = dead;
+  }
+  __syncthreads();
+  return *sdead != 0;
+}
+
+// ------------------------------------------------------------------------------------------------ attention
+// Item = (sequence, kv head, part of 256 keys, tile of 16 query rows); the query rows of a sequence are its R rows
+// times the G query heads of the group, row index qr = j * G + head-in-group.  Wave w of the unit takes keys
+// [256 part + 64 w, +64).  Scores are kept in the base-2 domain (scale * log2 e folded in), so that the
+// exponentials are single instructions.
+struct DAttItem {
+  int valid, b, kvh, part, rt, seq, len, nact, off, pos_last, nparts_b;
+  int koff[4], voff[2];
+};
+
+__device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int ntile, int uw, int lane) {
+  DAttItem it;
+  it.valid = item < a.n_seqs * a.nkv * a.n_parts * ntile;
+  it.b = 0; it.kvh = 0; it.part = 0; it.rt = 0;
+  if (it.valid) {
+    it.rt = item % ntile;
+    int t = item / ntile;
+    it.b = t % a.n_seqs;
+    t /= a.n_seqs;
+    it.kvh = t % a.nkv;
+    it.part = t / a.nkv;
+  }
+  it.seq = a.rows.seq0 + it.b;
+  it.len = __builtin_amdgcn_readfirstlane(ld_state(a.kv.len + it.seq));
+  const int npend = a.pcap ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.n_pend + it.seq)) : 0;
+  it.off = a.pcap - npend;
+  it.nact = a.rows.R - it.off;
+  it.pos_last = it.len + it.nact - 1;
+  it.valid = it.valid && it.part * ATT_PART <= it.pos_last;
+  it.nparts_b = it.pos_last / ATT_PART + 1;
+  const int kbase = it.part * ATT_PART + uw * 64;
+  const int g = lane >> 4, c16 = lane & 15;
+  int blk[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int bi = (kbase >> 4) + t;
+    const int b = (it.valid && bi < a.kv.mbps && bi * 16 <= it.pos_last)
+                      ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.table + it.seq * a.kv.mbps + bi)) : -1;
+    blk[t] = b < 0 ? 0 : b;                                    // masked keys may read any block
+    it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];
+    it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
+  }
+  return it;
+}
+
+// The 16 fragment loads of a wave's chunk from the pool.  Positions at or beyond the sequence's cached length hold
+// whatever an earlier launch left there; they are patched or masked later, never used.
+__device__ __forceinline__ void df_load_kv(const DArgs& a, int layer, const DAttItem& it, KVPre& kv) {
+  const size_t plane = (size_t)a.kv.n_blocks * a.kv.nkv * 1024;
+  const bf16_t* kp = (const bf16_t*)a.kv.pool + (size_t)(2 * layer) * plane;
+  const bf16_t* vp = kp + plane;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    kv.kf[t][0] = *(const u32x4*)(kp + it.koff[t]);
+    kv.kf[t][1] = *(const u32x4*)(kp + it.koff[t] + 32);
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) kv.vf[ks][dt] = *(const u32x4*)(vp + it.voff[ks] + dt * 256);
+}
+
+__device__ __forceinline__ float df_exp2(float x) { return __builtin_amdgcn_exp2f(x); }     // x <= 0 here, or -inf
+
+#ifdef SSD_TRACE_FINE
+#define DF_AFINE(k) do { if (a.trace && threadIdx.x == 0 && layer == 3) a.trace[(size_t)blockIdx.x * 512 + 256 + 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define DF_AFINE(k) do { } while (0)
+#endif
+
+__device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const DAttItem& it, uint32_t* lds,
+                                              const int* srow, int* sdead, int slot) {
+  DF_AFINE(0);
+  // The pool fragments are requested first: the queries of this layer are not there yet in any case.
+  KVPre kvp;
+  df_load_kv(a, layer, it, kvp);
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int usel = wave >> 2, uw = wave & 3, ut = tid & 255;
+  uint32_t* ub = lds + usel * DF_ATT_UNIT;
+  uint32_t* Qs = ub;                                   // [16 rows][64] operand words
+  bf16_t* Kn = (bf16_t*)(ub + 4096);                   // [16][64] new keys
+  bf16_t* Vn = (bf16_t*)(ub + 4096 + 512);             // [16][64] new values
+  float* Pw = (float*)(ub + 4096 + 1024) + uw * 1024;  // [16][64] per wave
+  float* MO = (float*)(ub + 4096 + 1024 + 4096);       // [4][16][64]
+  float* ML = (float*)(ub + 4096 + 1024 + 8192);       // [4][16][2]
+  const int R = a.rows.R, G = a.nq / a.nkv, nqd = a.nq * 64, RG = R * G;
+  const int g = lane >> 4, c16 = lane & 15;
+  const int kbase = it.part * ATT_PART + uw * 64;
+  const int r0 = 16 * it.rt, nrt = min(16, RG - r0);                         // first query row and rows of this tile
+  const bool wlive = it.valid && kbase <= it.pos_last;
+  const bool unew = it.valid && it.part * ATT_PART + ATT_PART > it.len;      // the part reaches this launch's positions
+  const u64* q = a.q + (size_t)layer * a.st_q;
+  const u64* kvn = a.kvn + (size_t)layer * a.st_kvn;
+  u64* attn = a.attn + (size_t)layer * a.st_q;
+  u64* att_p = a.att_p + (size_t)layer * a.st_att_p;
+  const int* rowpos = srow + it.b * R;                 // positions of the sequence's rows
+  const float sc2 = a.scale * 1.44269504088896340736f;
+  bool bad = false;
+  // ---- one flight per thread: the queries of the tile's rows and this launch's keys / values of the kv head
+  if (it.valid) {
+    const int nQ = nrt * 64, total = nQ + (unew ? it.nact * 128 : 0);       // <= 1024 + 2048 words
+    const uint32_t q_off = (uint32_t)(q - a.tw), n_off = (uint32_t)(kvn - a.tw);
+    uint32_t off[DF_B], out[DF_B];
+#pragma unroll
+    for (int u = 0; u < DF_B; ++u) {
+      const int idx = u * 256 + ut;
+      off[u] = 0xFFFFFFFFu;
+      if (idx < nQ) {
+        const int r = r0 + (idx >> 6), dd = idx & 63, j = r / G, gq = r - j * G;
+        off[u] = q_off + (uint32_t)((it.b * R + j) * nqd + (it.kvh * G + gq) * 64 + dd);
+      } else if (idx < total) {
+        const int i2 = idx - nQ, jn = i2 >> 7, which = (i2 >> 6) & 1, dd = i2 & 63;
+        off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
+      }
+    }
+    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64);
+#pragma unroll
+    for (int u = 0; u < DF_B; ++u) {
+      const int idx = u * 256 + ut;
+      if (idx < nQ) Qs[idx] = out[u];
+      else if (idx < total) {
+        const int i2 = idx - nQ, jn = i2 >> 7, which = (i2 >> 6) & 1, dd = i2 & 63;
+        (which ? Vn : Kn)[jn * 64 + dd] = (bf16_t)out[u];
+      }
+    }
+    for (int idx = nQ + ut; idx < 1024; idx += 256) Qs[idx] = 0u;           // padding rows of the tile
+  }
+  if (bad) *sdead = 1;
+  __syncthreads();
+  if (*sdead) return true;
+  DF_STAMP(slot);
+  DF_AFINE(1);
+  // ---- fragments of positions written by this launch come from the side buffer, at the pool's fragment slots
+  if (wlive && kbase + 64 > it.len) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int jn = kbase + 16 * t + c16 - it.len;
+      if ((unsigned)jn < (unsigned)it.nact) {
+        kvp.kf[t][0] = *(const u32x4*)(Kn + jn * 64 + g * 8);
+        kvp.kf[t][1] = *(const u32x4*)(Kn + jn * 64 + 32 + g * 8);
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const int dim = 16 * dt + c16;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          uint32_t x = kvp.vf[ks][dt][w];
+          const int j0 = kbase + 32 * ks + 8 * g + 2 * w - it.len, j1 = j0 + 1;
+          if ((unsigned)j0 < (unsigned)it.nact) x = (x & 0xFFFF0000u) | (uint32_t)Vn[j0 * 64 + dim];
+          if ((unsigned)j1 < (unsigned)it.nact) x = (x & 0x0000FFFFu) | ((uint32_t)Vn[j1 * 64 + dim] << 16);
+          kvp.vf[ks][dt][w] = x;
+        }
+      }
+  }
+  DF_AFINE(2);
+  float mrow[4], lrow[4];
+  f32x4 oacc[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { mrow[r] = -INFINITY; lrow[r] = 0.f; oacc[r] = f32x4{0, 0, 0, 0}; }
+  if (wlive) {
+    u32x4 qh[2], ql[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) frag_from_lds(Qs + c16 * 64 + ks * 32 + g * 8, qh[ks], ql[ks]);
+    f32x4 s[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bf16x8 k0 = __builtin_bit_cast(bf16x8, kvp.kf[t][0]), k1 = __builtin_bit_cast(bf16x8, kvp.kf[t][1]);
+      f32x4 z = f32x4{0, 0, 0, 0};
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ql[0]), k0, z, 0, 0, 0);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ql[1]), k1, z, 0, 0, 0);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[0]), k0, z, 0, 0, 0);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[1]), k1, z, 0, 0, 0);
+      s[t] = z;
+    }
+    // element (reg r, tile t) = (query row r0 + 4g + r, key kbase + 16t + c16)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int qr = r0 + 4 * g + r;
+      const int pos = qr < RG ? rowpos[qr / G] : -1;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const bool ok = kbase + 16 * t + c16 <= pos;
+        s[t][r] = ok ? s[t][r] * sc2 : -INFINITY;
+        mx = fmaxf(mx, s[t][r]);
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+      float sum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float p = (s[t][r] == -INFINITY) ? 0.f : df_exp2(s[t][r] - mx);
+        Pw[(4 * g + r) * 64 + 16 * t + c16] = p;
+        sum += p;
+      }
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, WAVE);
+      mrow[r] = mx;
+      lrow[r] = sum;
+    }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const u32x4* pp = (const u32x4*)(Pw + c16 * 64 + ks * 32 + g * 8);
+      const SplitA pf = split_bf16(pp[0], pp[1]);
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 vv = __builtin_bit_cast(bf16x8, kvp.vf[ks][dt]);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.lo, vv, oacc[dt], 0, 0, 0);
+        oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.hi, vv, oacc[dt], 0, 0, 0);
+      }
+    }
+  }
+  // ---- merge the unit's four chunks (ascending key order) and publish the part
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * g + r;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) MO[(uw * 16 + row) * 64 + 16 * dt + c16] = oacc[dt][r];
+    if (c16 == 0) { ML[(uw * 16 + row) * 2] = mrow[r]; ML[(uw * 16 + row) * 2 + 1] = lrow[r]; }
+  }
+  __syncthreads();
+  DF_AFINE(3);
+  {
+    const int row = ut >> 4, ch = ut & 15, d0 = ch * 4, qr = r0 + row;
+    if (it.valid && qr < RG) {
+      const int j = qr / G, gq = qr - j * G, m = it.b * R + j, head = it.kvh * G + gq;
+      const int np_row = rowpos[j] / ATT_PART + 1;
+      if (it.part < np_row) {
+        float mx = -INFINITY;
+        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, ML[(w * 16 + row) * 2]);
+        float l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < 4; ++w) {
+          const float mw = ML[(w * 16 + row) * 2];
+          if (mw == -INFINITY) continue;
+          const float e = df_exp2(mw - mx);
+          l = fmaf(ML[(w * 16 + row) * 2 + 1], e, l);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = fmaf(MO[(w * 16 + row) * 64 + d0 + i], e, o[i]);
+        }
+        if (np_row == 1) {                                  // a single part: this is the result
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+        } else {
+          u64* pp = att_p + ((((size_t)m * a.nq + head) * a.NP + it.part) * 16 + ch) * 6;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st_wordf(pp + i, o[i], a.tag);
+          st_wordf(pp + 4, mx, a.tag);
+          st_wordf(pp + 5, l, a.tag);
+        }
+      }
+    }
+  }
+  // ---- merge of the parts: of the tile's rows, the unit of part p finishes those with row index = p mod P
+  if (it.valid && it.nparts_b > 1) {
+    const int P = it.nparts_b;
+    const int ri = ut >> 4, ch = ut & 15, d0 = ch * 4;
+    const int first = ((it.part - r0) % P + P) % P;                          // first row of the tile this unit finishes
+    const int qr = r0 + first + ri * P;
+    if (first + ri * P < nrt) {
+      const int j = qr / G, gq = qr - j * G, m = it.b * R + j, head = it.kvh * G + gq;
+      const int np_row = rowpos[j] / ATT_PART + 1;
+      if (np_row > 1) {
+        const uint32_t p_off = (uint32_t)(att_p - a.tw) + (uint32_t)(((m * a.nq + head) * a.NP) * 96 + ch * 6);
+        float mx = -INFINITY, l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int p0 = 0; p0 < np_row; p0 += DF_NPF) {
+          uint32_t out[DF_NPF * 6];
+          bad = !poll_parts(a.tw, p_off + (uint32_t)(p0 * 96), np_row - p0, a.tag, out, a.bar + 64) || bad;
+          float gm = mx;
+#pragma unroll
+          for (int p = 0; p < DF_NPF; ++p)
+            if (p0 + p < np_row) gm = fmaxf(gm, __uint_as_float(out[p * 6 + 4]));
+          if (p0 > 0) {                                      // more than DF_NPF parts: rescale what is already summed
+            const float e = df_exp2(mx - gm);
+            l *= e;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] *= e;
+          }
+          mx = gm;
+#pragma unroll
+          for (int p = 0; p < DF_NPF; ++p)
+            if (p0 + p < np_row) {
+              const float e = df_exp2(__uint_as_float(out[p * 6 + 4]) - mx);
+              l = fmaf(__uint_as_float(out[p * 6 + 5]), e, l);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) o[i] = fmaf(__uint_as_float(out[p * 6 + i]), e, o[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+      }
+    }
+  }
+  DF_STAMP(slot + 1);
+  DF_AFINE(4);
+  if (bad) *sdead = 1;
+  __syncthreads();
+  DF_AFINE(5);
+  return *sdead != 0;
+}
+
+// ------------------------------------------------------------------------------------------------ the kernel
+__global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
+  __shared__ __attribute__((aligned(16))) uint32_t lds[DF_LDS_WORDS];
+  __shared__ int srow[3 * 16];
+  __shared__ int sdead;
+  if (threadIdx.x == 0) sdead = 0;
+  const int nqkv = (a.nq + 2 * a.nkv) * 64, nqd = a.nq * 64, L = a.n_layers, np = a.d >> 5;
+  const int NU = gridDim.x * 2;
+  // items of every phase kind, and the unit that takes item 0 (the kinds with few items go to different workgroups)
+  const int n_qkv = (a.nq + 2 * a.nkv) * 2, ntile = (a.rows.R * (a.nq / a.nkv) + 15) >> 4,
+            n_att = a.n_seqs * a.nkv * a.n_parts * ntile, n_o = np * a.gs_o, n_gu = a.ffn >> 4,
+            n_dn = np * a.gs_d, n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
+  const int s_att = n_qkv % NU, s_o = (n_qkv + n_att) % NU, s_dn = (n_qkv + n_att + n_o) % NU;
+  auto make_qkv = [&](int l) {
+    const PLayer Y = layer_ptrs(a, l);
+    DPhase x = DPhase{};
+    x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
+    x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = 0;
+    x.bias = Y.bqkv; x.out = a.q + (size_t)l * a.st_q; x.kvn = a.kvn + (size_t)l * a.st_kvn;
+    return x;
+  };
+  auto make_resid = [&](int l, int second) {
+    const PLayer Y = layer_ptrs(a, l);
+    DPhase x = DPhase{};
+    x.layer = l;
+    x.A = second ? a.act + (size_t)l * a.st_act : a.attn + (size_t)l * a.st_q;
+    x.W0 = second ? Y.wdown : Y.wo; x.W1 = x.W0; x.N = a.d; x.K = second ? a.ffn : nqd;
+    x.gs = second ? a.gs_d : a.gs_o; x.items = np * x.gs; x.shift = second ? s_dn : s_o;
+    const size_t hi = (size_t)(2 * l + second);
+    x.h_in = a.h + hi * a.st_h; x.h_out = a.h + (hi + 1) * a.st_h; x.hg_out = a.hg + (hi + 1) * a.st_h;
+    x.sq_out = a.sq + (hi + 1) * a.st_sq;
+    x.gain_next = second ? (l + 1 < L ? layer_ptrs(a, l + 1).ln1 : a.final_norm) : Y.ln2;
+    x.part = a.part + hi * a.st_part;
+    return x;
+  };
+  auto make_swiglu = [&](int l) {
+    const PLayer Y = layer_ptrs(a, l);
+    DPhase x = DPhase{};
+    x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
+    x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0;
+    x.out = a.act + (size_t)l * a.st_act;
+    return x;
+  };
+  auto make_head = [&]() {
+    DPhase x = DPhase{};
+    x.A = a.hg + (size_t)(2 * L) * a.st_h; x.sq = a.sq + (size_t)(2 * L) * a.st_sq;
+    x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.logits = a.logits;
+    return x;
+  };
+  // which phase kinds this wave's unit / this workgroup has a round-0 item in
+  const int wave_k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int unit = blockIdx.x * 2 + (wave_k >> 2);
+  auto has = [&](int u, int shift, int items) { return df_item_of_unit(u, shift, NU) < items; };
+  const bool u_q = has(unit, 0, n_qkv), u_o = has(unit, s_o, n_o), u_g = has(unit, 0, n_gu), u_d = has(unit, s_dn, n_dn),
+             u_l = a.with_head && has(unit, 0, n_lg);
+  const int u0 = blockIdx.x * 2, u1 = u0 + 1;
+  const bool g_q = has(u0, 0, n_qkv) || has(u1, 0, n_qkv), g_a = has(u0, s_att, n_att) || has(u1, s_att, n_att),
+             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = has(u0, 0, n_gu) || has(u1, 0, n_gu) || n_gu > NU,
+             g_d = has(u0, s_dn, n_dn) || has(u1, s_dn, n_dn), g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
+
+  WPre w;
+  int w_for = -1;                     // phase (5 * layer + kind; 5L: head) whose weights `w` holds
+  // Request the weights of the unit's first item at or after phase `from` (kinds 0 QKV, 2 O, 3 gate/up, 4 down).
+  auto prefetch_from = [&](int from) {
+    DPhase x = DPhase{};
+    int epi = -1, at = -1;
+    for (int ph = from; ph <= 5 * L && ph < from + 6 && epi < 0; ++ph) {
+      const int l = ph / 5, k = ph - l * 5;
+      at = ph;
+      if (ph == 5 * L) { if (u_l) { x = make_head(); epi = PE_LOGITS; } break; }
+      if (k == 0 && u_q) { x = make_qkv(l); epi = PE_QKV; }
+      else if (k == 2 && u_o) { x = make_resid(l, 0); epi = PE_RESID; }
+      else if (k == 3 && u_g) { x = make_swiglu(l); epi = PE_SWIGLU; }
+      else if (k == 4 && u_d) { x = make_resid(l, 1); epi = PE_RESID; }
+    }
+    if (epi >= 0) { df_prefetch(x, epi, w); w_for = at; }
+  };
+
+  df_embed_phase(a);
+  prefetch_from(0);
+  if (df_start_barrier(a, &sdead)) return;
+  const DAttItem ait = df_att_item(a, df_item_of_unit(unit, s_att, NU), ntile, wave_k & 3, threadIdx.x & 63);
+  if (threadIdx.x < a.rows.M) {                           // per-row constants of the launch: position, active, block of the new key
+    const int m = threadIdx.x;
+    const int pos = ld_state(a.rows.pos + m);
+    srow[m] = pos;
+    srow[16 + m] = ld_state(a.rows.active + m);
+    srow[32 + m] = (pos >> 4) < a.kv.mbps ? ld_state(a.kv.table + (a.rows.seq0 + m / a.rows.R) * a.kv.mbps + (pos >> 4)) : -1;
+  }
+  __syncthreads();
+  DF_STAMP(0);
+  for (int l = 0; l < L; ++l) {
+    const int s0 = 2 + l * 10, p0 = 5 * l;
+    if (g_q) {
+      const DPhase cur = make_qkv(l);
+      if (df_gemm_phase<PE_QKV>(a, cur, w, w_for == p0, lds, srow, &sdead, s0, [&]() { if (w_for < p0 + 1) prefetch_from(p0 + 1); })) return;
+    }
+    if (g_a) {
+      if (df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
+    }
+    if (g_o) {
+      const DPhase cur = make_resid(l, 0);
+      if (df_gemm_phase<PE_RESID>(a, cur, w, w_for == p0 + 2, lds, srow, &sdead, s0 + 4, [&]() { if (w_for < p0 + 3) prefetch_from(p0 + 3); })) return;
+    }
+    if (g_g) {
+      const DPhase cur = make_swiglu(l);
+      if (df_gemm_phase<PE_SWIGLU>(a, cur, w, w_for == p0 + 3, lds, srow, &sdead, s0 + 6, [&]() { if (w_for < p0 + 4) prefetch_from(p0 + 4); })) return;
+    }
+    if (g_d) {
+      const DPhase cur = make_resid(l, 1);
+      if (df_gemm_phase<PE_RESID>(a, cur, w, w_for == p0 + 4, lds, srow, &sdead, s0 + 8, [&]() { if (w_for < p0 + 5) prefetch_from(p0 + 5); })) return;
+    }
+  }
+  if (a.with_head && g_l) {
+    const DPhase cur = make_head();
+    df_gemm_phase<PE_LOGITS>(a, cur, w, w_for == 5 * L, lds, srow, &sdead, 2 + L * 10, []() {});
+  }
+}
+
+}  // namespace ssd

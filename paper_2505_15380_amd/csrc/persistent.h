@@ -101,7 +101,8 @@ struct PArgs {
   unsigned long long* trace;   // optional [gridDim.x][512] clock samples (arrive / leave per barrier), or null
 };
 
-__device__ __forceinline__ PLayer layer_ptrs(const PArgs& a, int l) {
+template <typename AR>
+__device__ __forceinline__ PLayer layer_ptrs(const AR& a, int l) {
   const size_t o = (size_t)l * a.layer_stride;
   PLayer y;
   y.wqkv = (const char*)a.layer0.wqkv + o; y.wo = (const char*)a.layer0.wo + o; y.wgate = (const char*)a.layer0.wgate + o;
@@ -200,8 +201,8 @@ struct WPre {             // weight fragments of a wave's first PF_K k-tiles of 
   u32x4 b0[PF_K], b1[PF_K];
 };
 
-template <int EPI>
-__device__ __forceinline__ bool gemm_item(const GemmPhase& ph, int item, int& t0, int& t1, int& split) {
+template <int EPI, typename PH>
+__device__ __forceinline__ bool gemm_item(const PH& ph, int item, int& t0, int& t1, int& split) {
   t0 = 0; t1 = 0; split = 0;
   if (item >= ph.items) return false;
   if (EPI == PE_QKV) {
@@ -219,7 +220,8 @@ __device__ __forceinline__ bool gemm_item(const GemmPhase& ph, int item, int& t0
 }
 
 // k-tiles [kb, ke) of wave uw (0..3) of the unit that owns global split `split`
-__device__ __forceinline__ void wave_krange(const GemmPhase& ph, int split, int uw, int& kb, int& ke) {
+template <typename PH>
+__device__ __forceinline__ void wave_krange(const PH& ph, int split, int uw, int& kb, int& ke) {
   const int KT = ph.K >> 5;
   const int per_s = KT / ph.gs, rem_s = KT - per_s * ph.gs;
   const int wg_b = split * per_s + min(split, rem_s), wg_n = per_s + (split < rem_s ? 1 : 0);
@@ -229,8 +231,8 @@ __device__ __forceinline__ void wave_krange(const GemmPhase& ph, int split, int 
 }
 
 // Exactly 2*PF_K loads: the wave's first PF_K k-tiles of its round-0 item, or the first tile again where it has fewer.
-template <int EPI>
-__device__ __forceinline__ void prefetch_weights(const GemmPhase& ph, WPre& pre) {
+template <int EPI, typename PH>
+__device__ __forceinline__ void prefetch_weights(const PH& ph, WPre& pre) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform: scalar registers

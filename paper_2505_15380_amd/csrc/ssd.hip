@@ -17,6 +17,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "persistent.h"
+#include "dataflow.h"
 #include "sample.h"
 
 using namespace ssd;
@@ -302,6 +303,10 @@ struct ssd_kv {
   int NP, p_rows;
   uint32_t epoch = 0;
   int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
+  // tagged workspace of the barrier-free forward (see dataflow.h); null when that kernel is not usable
+  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_act, *t_part, *t_att_p;
+  size_t t_words = 0;
+  bool dataflow = false;
   // host
   int32_t* mirror_host;
   std::vector<int> len_ub, npend_ub;
@@ -348,7 +353,19 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   int32_t* tickets = cv.take<int32_t>(std::max(c.d_model / 32 + 1, Mmax * c.n_kv_heads));
   uint32_t* bar = cv.take<uint32_t>(128);
   unsigned long long* trace = cv.take<unsigned long long>(p_ok ? 256 * 512 : 0);
+  // tagged words of the barrier-free forward: one block, zeroed at creation
+  const size_t TR = PR;
+  const size_t w_h = (size_t)(2 * L + 1) * TR * c.d_model, w_sq = (size_t)(2 * L + 1) * TR * (c.d_model / 32);
+  const size_t w_q = (size_t)L * TR * nqd, w_kvn = (size_t)L * TR * 2 * c.n_kv_heads * 64, w_act = (size_t)L * TR * c.d_ffn;
+  const size_t w_part = (size_t)2 * L * P_MAX_SPLITS * TR * c.d_model, w_attp = (size_t)L * TR * c.n_q_heads * NP * 96;
+  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_act + w_part + w_attp;
+  u64* t_base = cv.take<u64>(t_words);
   if (kv) {
+    u64* t = t_base;
+    kv->t_base = t_base; kv->t_words = t_words;
+    kv->t_h = t; t += w_h; kv->t_hg = t; t += w_h; kv->t_sq = t; t += w_sq; kv->t_q = t; t += w_q; kv->t_attn = t; t += w_q;
+    kv->t_kvn = t; t += w_kvn; kv->t_act = t; t += w_act; kv->t_part = t; t += w_part; kv->t_att_p = t;
+
     kv->trace = trace;
     kv->p_h = p_h; kv->p_hg = p_hg; kv->p_sumsq = p_sumsq; kv->p_q = p_q; kv->p_attn = p_attn; kv->p_act = p_act; kv->p_part = p_part; kv->p_att_o = p_att_o;
     kv->p_att_ml = p_att_ml; kv->tickets = tickets; kv->bar = bar; kv->NP = NP; kv->p_rows = PR;
@@ -423,6 +440,13 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
       if (const char* env = getenv("SSD_PERSISTENT_WGS")) want = atoi(env);
       kv->persistent_wgs = std::max(0, std::min(want, cus));        // one workgroup per CU at most: all co-resident
     }
+  }
+  // The barrier-free forward additionally needs its word offsets to fit 32 bits; its words start untagged (zero).
+  kv->dataflow = false;
+  if (e == hipSuccess && kv->persistent_wgs > 0 && kv->t_words > 0 && kv->t_words < ((size_t)1 << 32)) {
+    e = hipMemsetAsync(kv->t_base, 0, kv->t_words * sizeof(u64), (hipStream_t)stream);
+    const char* env = getenv("SSD_FORWARD");
+    kv->dataflow = !(env && strcmp(env, "barrier") == 0);
   }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
@@ -537,6 +561,52 @@ static int forward_persistent(const ssd_model* m, ssd_kv* kv, Rows rows, int B, 
   return SSD_OK;
 }
 
+// The same forward without grid barriers between phases (see dataflow.h).  Returns -1 when the launch does not
+// fit that kernel's limits, so that the caller takes the barrier kernel instead.
+static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, int pcap, const int32_t* dev_tokens,
+                            int tok_stride, bool with_head, hipStream_t st) {
+  const ssd_model_config& c = m->c;
+  const int G = kv->persistent_wgs, NU = 2 * G, npairs = c.d_model / 32, M = rows.M;
+  const int nqd = c.n_q_heads * c.head_dim, grp = c.n_q_heads / c.n_kv_heads;
+  auto splits = [&](int K) { return std::max(1, std::min(std::min(NU / npairs, (K / 32) / 4), P_MAX_SPLITS)); };
+  const int gs_o = nqd / 32 <= 4 * PF_K ? 1 : splits(nqd), gs_d = splits(c.d_ffn);
+  int max_len = 0;
+  for (int s = rows.seq0; s < rows.seq0 + B; ++s) max_len = std::max(max_len, kv->len_ub[s]);
+  const int n_parts = std::min(kv->NP, cdiv(max_len + rows.R, ATT_PART));
+  // limits: one round of attention and of the k-split projections (a unit that reduces must not wait for itself),
+  // query rows of an item, LDS staging capacity
+  auto kn_max = [&](int K, int gs) { return cdiv(K / 32, gs) * 32; };
+  const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU && npairs * gs_o <= NU &&
+                    npairs * gs_d <= NU && M * (c.d_model + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
+                    (gs_o == 1 ? M * (nqd + 4) <= DF_AW : M * (kn_max(nqd, gs_o) + 4) <= DF_AW / 2) &&
+                    (gs_d == 1 ? M * (c.d_ffn + 4) <= DF_AW : M * (kn_max(c.d_ffn, gs_d) + 4) <= DF_AW / 2) &&
+                    2 + 10 * c.n_layers + 2 <= 512;
+  if (!fits) return -1;
+  DArgs a;
+  memset(&a, 0, sizeof a);
+  a.n_layers = c.n_layers; a.d = c.d_model; a.nq = c.n_q_heads; a.nkv = c.n_kv_heads; a.ffn = c.d_ffn; a.vocab = c.vocab;
+  a.n_embed = c.n_embed; a.eps = c.rms_eps; a.scale = 1.0f / sqrtf((float)c.head_dim);
+  a.embed = (const bf16_t*)m->embed; a.final_norm = m->final_norm; a.head = m->head; a.rope = m->rope;
+  a.layer0 = m->host_layers[0];
+  a.layer_stride = m->layer_stride;
+  a.kv = kv->v; a.rows = rows; a.pcap = pcap; a.n_seqs = B; a.tok_stride = tok_stride; a.with_head = with_head ? 1 : 0;
+  a.tokens = dev_tokens;
+  const size_t PR = kv->p_rows;
+  a.tw = kv->t_base; a.h = kv->t_h; a.hg = kv->t_hg; a.sq = kv->t_sq; a.q = kv->t_q; a.kvn = kv->t_kvn; a.attn = kv->t_attn;
+  a.act = kv->t_act; a.part = kv->t_part; a.att_p = kv->t_att_p; a.logits = kv->logits;
+  a.st_h = PR * c.d_model; a.st_sq = PR * (c.d_model / 32); a.st_q = PR * nqd; a.st_kvn = PR * 2 * c.n_kv_heads * 64;
+  a.st_act = PR * c.d_ffn; a.st_part = (size_t)P_MAX_SPLITS * PR * c.d_model; a.part_stride = PR * c.d_model;
+  a.st_att_p = PR * c.n_q_heads * kv->NP * 96;
+  a.NP = kv->NP; a.n_parts = n_parts; a.gs_o = gs_o; a.gs_d = gs_d;
+  a.bar = kv->bar;
+  a.tag = ++kv->epoch;
+  a.trace = kv->trace_on ? kv->trace : nullptr;
+  ProfScope ps(PROF_PERSISTENT, st);
+  hipLaunchKernelGGL(k_forward_dataflow, dim3(G), dim3(PBLOCK), 0, st, a);
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
 // One decoder forward for sequences [seq0, seq0+B), R rows each.  pcap = pending slots at the head of each
 // sequence's rows (0: all rows take explicit tokens).  Leaves logits [B*R][vocab] in the workspace when
 // with_head.  The caller has checked room.
@@ -548,7 +618,13 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   const int nqd = nq * hd, nqkv = m->n_qkv();
   Rows rows = kv->rows;
   rows.M = M; rows.R = R; rows.seq0 = seq0;
-  if (kv->persistent_wgs > 0 && M <= kv->p_rows) return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
+  if (kv->persistent_wgs > 0 && M <= kv->p_rows) {
+    if (kv->dataflow) {
+      const int rc = forward_dataflow(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
+      if (rc >= 0) return rc;
+    }
+    return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
+  }
 
   EmbedArgs e;
   e.kv = kv->v; e.rows = rows; e.pcap = pcap; e.n_seqs = B; e.tokens = dev_tokens; e.tok_stride = tok_stride;
