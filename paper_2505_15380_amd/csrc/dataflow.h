@@ -44,6 +44,13 @@ constexpr int DF_ATT_UNIT = 4096 + 512 + 512 + 4096 + 4096 + 128;      // Q | ne
 constexpr int DF_LDS_WORDS = (DF_AW + DF_SQ_WORDS + DF_RED_WORDS) > 2 * DF_ATT_UNIT ? (DF_AW + DF_SQ_WORDS + DF_RED_WORDS)
                                                                                   : 2 * DF_ATT_UNIT;
 
+#ifndef DF_QKV_LOCAL
+#define DF_QKV_LOCAL 0          // 1: the QKV phase keeps its weights in registers of its own; 0: in the shared prefetch buffer
+#endif
+#ifndef DF_O_MODE
+#define DF_O_MODE 0             // 0: output projection weights in the shared prefetch buffer; 2: L2 warm-up + in-phase loads
+#endif
+
 struct DArgs {
   int n_layers, d, nq, nkv, ffn, vocab, n_embed;
   float eps, scale;
@@ -68,6 +75,9 @@ struct DArgs {
   u64* act;               // [L][PR][ffn]       operand: SwiGLU output
   u64* part;              // [2L][P_MAX_SPLITS][PR][d] fp32: k-split partials (splits >= 1) of the output / down projections
   u64* att_p;             // [L][PR][nq][NP][16][6] fp32: per part and 4-dim chunk: 4 weighted values, max, sum
+  u64* part2;             // [2][ffn/32][PR][d] fp32: down-projection partials of one 32-column slice of the SwiGLU output each,
+                          // tagged with launch and layer (buffer = layer parity)
+  size_t st_part2;
   float* logits;
   size_t st_h, st_sq, st_q, st_kvn, st_act, st_part, st_att_p, part_stride;   // strides in words
   int NP, n_parts, gs_o, gs_d;
@@ -164,36 +174,63 @@ struct DPhase {
 };
 
 // Operand words [k0, k0+kn) of rows [0, M) (row stride K words) -> As[row * (kn + 4) + k - k0], and the rows' sums of
-// squares [M][KT] -> sqs.  Thread gt of gn; the whole group polls in parallel.
+// squares [M][KT] -> sqs.  Thread gt of gn; the whole group polls in parallel.  Two more words per thread (x0, x1:
+// offsets, or ~0) ride in the first flight and come back in xo0, xo1.  Word offsets are recomputed for a repeated
+// load instead of being kept in registers.
 __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, int k0, int kn, const u64* sq, int KT,
-                                              uint32_t* As, float* sqs, int gt, int gn) {
+                                              uint32_t* As, float* sqs, int gt, int gn, uint32_t x0, uint32_t x1,
+                                              uint32_t& xo0, uint32_t& xo1) {
   const int M = a.rows.M, nA = M * kn, total = nA + (sq ? M * KT : 0), stride = kn + 4;
   const uint32_t a_off = (uint32_t)(A - a.tw), s_off = sq ? (uint32_t)(sq - a.tw) : 0u;
+  const float rkn = 1.0f / (float)kn;
+  const uint32_t tag = a.tag;
+  uint32_t* err = a.bar + 64;
   bool ok = true;
-  for (int base = 0; base < total; base += gn * DF_B) {
-    uint32_t off[DF_B], out[DF_B];
+  for (int base = 0; base < total || base == 0; base += gn * DF_B) {
+    int g2 = gt;
+    auto off_of = [&](int u) -> uint32_t {
+      if (u >= DF_B) return base == 0 ? (u == DF_B ? x0 : x1) : 0xFFFFFFFFu;
+      const int idx = base + u * gn + g2;
+      if (idx < nA) {
+        const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
+        return a_off + (uint32_t)(row * K + k0 + k);
+      }
+      return idx < total ? s_off + (uint32_t)(idx - nA) : 0xFFFFFFFFu;
+    };
+    u64 v[DF_B + 2];
+#pragma unroll
+    for (int u = 0; u < DF_B + 2; ++u) {
+      const uint32_t o = off_of(u);
+      v[u] = o != 0xFFFFFFFFu ? ld_word(a.tw + o) : ((u64)tag << 32);
+    }
+    long spins = 0;
+    for (;;) {
+      bool all = true;
+#pragma unroll
+      for (int u = 0; u < DF_B + 2; ++u) all = all && ((uint32_t)(v[u] >> 32) == tag);
+      if (all) break;
+      if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
+        __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
+        ok = false;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+      asm volatile("" : "+v"(g2));                       // keeps the offsets out of registers across the wait
+#pragma unroll
+      for (int u = 0; u < DF_B + 2; ++u)
+        if ((uint32_t)(v[u] >> 32) != tag) v[u] = ld_word(a.tw + off_of(u));
+    }
 #pragma unroll
     for (int u = 0; u < DF_B; ++u) {
       const int idx = base + u * gn + gt;
-      off[u] = 0xFFFFFFFFu;
       if (idx < nA) {
-        const int row = idx / kn, k = idx - row * kn;
-        off[u] = a_off + (uint32_t)(row * K + k0 + k);
+        const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
+        As[row * stride + k] = (uint32_t)v[u];
       } else if (idx < total) {
-        off[u] = s_off + (uint32_t)(idx - nA);
+        sqs[idx - nA] = __uint_as_float((uint32_t)v[u]);
       }
     }
-    ok = poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64) && ok;
-#pragma unroll
-    for (int u = 0; u < DF_B; ++u) {
-      const int idx = base + u * gn + gt;
-      if (idx < nA) {
-        const int row = idx / kn, k = idx - row * kn;
-        As[row * stride + k] = out[u];
-      } else if (idx < total) {
-        sqs[idx - nA] = __uint_as_float(out[u]);
-      }
-    }
+    if (base == 0) { xo0 = (uint32_t)v[DF_B]; xo1 = (uint32_t)v[DF_B + 1]; }
   }
   return ok;
 }
@@ -254,7 +291,7 @@ __device__ __forceinline__ void df_prefetch(const DPhase& ph, int epi, WPre& pre
 // weight fragments of the unit's round-0 item (requested one or more phases earlier).  `after` is called once the
 // products of round 0 are issued and `pre` is free again (for the unit that sums the splits: after its wait for them).
 // Returns true if the workgroup has to leave (timeout somewhere in the grid).
-template <int EPI, typename FAfter>
+template <int EPI, int LOCALW, bool SPLITS, typename FAfter>
 __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, const WPre& pre, bool pre_ok, uint32_t* lds,
                                               const int* srow, int* sdead, int slot, FAfter&& after) {
   int tid = threadIdx.x;
@@ -282,24 +319,47 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     const bool live = valid && row < M;
     const bool reducer = EPI == PE_RESID && valid && split == 0;
     const int n0 = t0 * 16 + col, n1 = t1 * 16 + col;
-    // the residual input of the unit that finishes the rows was written a phase or more ago: request it now
-    u64 hw0 = 0, hw1 = 0;
-    if (reducer && row < M) {
-      hw0 = ld_word(ph.h_in + (size_t)row * ph.N + n0);
-      hw1 = ld_word(ph.h_in + (size_t)row * ph.N + n1);
+    // A phase with few items (LOCALW) requests its weights here, into registers of its own: its units arrive long
+    // before their operands do, and `pre` keeps the weights of the unit's next large phase.
+    WPre wl;
+    uint32_t warm0 = 0u, warm1 = 0u;
+    if (LOCALW == 2 && rd == 0 && valid) {
+      // one dword of each 128-byte line of the wave's weight fragments: brings them into this XCD's L2 while the
+      // unit waits for its operands; the real loads after that wait are L2 hits
+      const char* b0 = (const char*)ph.W0 + ((size_t)t0 * KT + kb) * 1024;
+      const char* b1 = (const char*)ph.W1 + ((size_t)(has1 ? t1 : t0) * KT + kb) * 1024;
+      const int nl = (ke - kb) * 8;                                  // lines per tile
+      if (lane < nl) warm0 = *(const volatile uint32_t*)(b0 + lane * 128);
+      if (lane < nl) warm1 = *(const volatile uint32_t*)(b1 + lane * 128);
     }
-    // ---- operands
+    if (LOCALW == 1 && rd == 0 && valid) {
+      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
+      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
+#pragma unroll
+      for (int u = 0; u < PF_K; ++u) {
+        const int kt = (kb + u < ke) ? kb + u : kb;
+        wl.b0[u] = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
+        wl.b1[u] = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+      }
+    }
+    // ---- operands; the unit that finishes the rows takes its residual inputs in the same flight
+    uint32_t hx0 = 0xFFFFFFFFu, hx1 = 0xFFFFFFFFu, hv0 = 0u, hv1 = 0u;
+    if (reducer && row < M) {
+      const uint32_t h_off = (uint32_t)(ph.h_in - a.tw) + (uint32_t)(row * ph.N);
+      hx0 = h_off + n0;
+      hx1 = h_off + n1;
+    }
     int k0 = 0, kn = ph.K;
     const uint32_t* Au = As;
     bool ok = true;
     if (shared) {
-      if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK);
+      if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1);
     } else {
       const int per_s = KT / ph.gs, rem_s = KT - per_s * ph.gs;
       k0 = (split * per_s + min(split, rem_s)) * 32;
       kn = (per_s + (split < rem_s ? 1 : 0)) * 32;
       Au = As + usel * (DF_AW / 2);
-      if (valid) ok = stage_operand(a, ph.A, ph.K, k0, kn, nullptr, 0, (uint32_t*)Au, sqs, ut, 256);
+      if (valid) ok = stage_operand(a, ph.A, ph.K, k0, kn, nullptr, 0, (uint32_t*)Au, sqs, ut, 256, hx0, hx1, hv0, hv1);
     }
     if (!ok) *sdead = 1;
     __syncthreads();
@@ -324,13 +384,15 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     if (valid) {
       const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
       const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
-      if (rd == 0 && pre_ok) {
+      if (LOCALW == 2) asm volatile("" :: "v"(warm0), "v"(warm1));
+      if (rd == 0 && (LOCALW == 1 || pre_ok)) {
 #pragma unroll
         for (int u = 0; u < PF_K; ++u)
           if (kb + u < ke) {
             u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
             if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
-            mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
+            if (LOCALW == 1) mfma_pair(xh, xl, wl.b0[u], wl.b1[u], acc0, acc1);
+            else mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
           }
       } else {
 #pragma unroll
@@ -427,17 +489,16 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
             off[2 * (s - 1)] = use ? p_off + (uint32_t)(s * a.part_stride) + n0 : 0xFFFFFFFFu;
             off[2 * (s - 1) + 1] = use ? p_off + (uint32_t)(s * a.part_stride) + n1 : 0xFFFFFFFFu;
           }
-          const uint32_t h_off = (uint32_t)(ph.h_in - a.tw) + (uint32_t)(row * ph.N);
-          const bool h_ok = (uint32_t)(hw0 >> 32) == a.tag && (uint32_t)(hw1 >> 32) == a.tag;
-          off[NW - 2] = h_ok ? 0xFFFFFFFFu : h_off + n0;
-          off[NW - 1] = h_ok ? 0xFFFFFFFFu : h_off + n1;
-          if (ph.gs > 1 || !h_ok) {
+          off[NW - 2] = 0xFFFFFFFFu;
+          off[NW - 1] = 0xFFFFFFFFu;
+          if (SPLITS && ph.gs > 1) {
             if (!poll_words<NW>(a.tw, off, a.tag, out, a.bar + 64)) *sdead = 1;
           }
-          if (h_ok) { out[NW - 2] = (uint32_t)hw0; out[NW - 1] = (uint32_t)hw1; }
+          out[NW - 2] = hv0;
+          out[NW - 1] = hv1;
 #pragma unroll
           for (int s = 1; s < P_MAX_SPLITS; ++s)
-            if (s < ph.gs) { v0 += __uint_as_float(out[2 * (s - 1)]); v1 += __uint_as_float(out[2 * (s - 1) + 1]); }
+            if (SPLITS && s < ph.gs) { v0 += __uint_as_float(out[2 * (s - 1)]); v1 += __uint_as_float(out[2 * (s - 1) + 1]); }
           v0 += __uint_as_float(out[NW - 2]);
           v1 += __uint_as_float(out[NW - 1]);
           st_wordf(ph.h_out + (size_t)row * ph.N + n0, v0, a.tag);
@@ -463,6 +524,228 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     if (*sdead) return true;
     DF_FINE(6);
   }
+  return false;
+}
+
+// ------------------------------------------------------------------------------------------------ fused MLP
+// Gate/up + SwiGLU + down projection inside one workgroup: its two units produce 32 consecutive columns of the
+// SwiGLU output, which is exactly one k-tile of the down projection; the workgroup multiplies it with that k-tile of
+// every output tile (8 waves x DF_DN tiles) and publishes a partial of the whole row.  The SwiGLU output never
+// leaves the workgroup, and one dependency per layer disappears; the price is ffn/32 partials per output.
+constexpr int DF_DN = 7;                  // down-projection output tiles a wave keeps prefetched
+struct WDown { u32x4 b[DF_DN]; };
+
+__device__ __forceinline__ uint32_t df_tag2(const DArgs& a, int layer) { return a.tag * 128u + (uint32_t)layer; }
+
+// Fragments (n-tile wave + 8 i, k-tile kt2) of the down projection for i < DF_DN; exactly DF_DN loads.
+__device__ __forceinline__ void df_prefetch_down(const DArgs& a, const void* wdown, int kt2, WDown& wd) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ntiles = a.d >> 4, KTd = a.ffn >> 5;
+#pragma unroll
+  for (int i = 0; i < DF_DN; ++i) {
+    const int nt = (wave + 8 * i < ntiles) ? wave + 8 * i : wave;
+    wd.b[i] = __builtin_nontemporal_load((const u32x4*)wdown + ((size_t)nt * KTd + kt2) * 64 + lane);
+  }
+}
+
+__device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, const void* wdown, u64* part2, uint32_t tag2,
+                                             uint32_t* lds, uint32_t* sact, int* sdead, int slot) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int usel = wave >> 2, uw = wave & 3, ut = tid & 255;
+  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  uint32_t* As = lds;
+  float* sqs = (float*)(lds + DF_AW);
+  float (*red)[2][256] = (float (*)[2][256])((float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048);
+  const int M = a.rows.M, PR = (int)(a.st_h / a.d);
+  const int KT = ph.K >> 5, ntiles_d = a.d >> 4, KTd = a.ffn >> 5;
+  const int arow = lane & 15, g = lane >> 4, c16 = lane & 15;
+  const int row = ut >> 4, col = ut & 15;
+  const int rounds = (ph.items + NU - 1) / NU;
+  for (int rd = 0; rd < rounds; ++rd) {
+    const int item = rd * NU + unit;
+    const bool valid = item < ph.items;
+    const int kt2 = item >> 1;                          // the workgroup's k-tile of the down projection
+    int kb = 0, ke = 0;
+    if (valid) wave_krange(ph, 0, uw, kb, ke);
+    const bool live = valid && row < M;
+    const int n0 = item * 16 + col;
+    // the weights of the unit's item and the workgroup's down-projection tiles: requested at entry, they arrive
+    // while the workgroup waits for its operands
+    WPre pre;
+    WDown wd;
+    if (valid) {
+      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)item * KT * 64 + lane;
+      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)item * KT * 64 + lane;
+#pragma unroll
+      for (int u = 0; u < PF_K; ++u) {
+        const int kt = (kb + u < ke) ? kb + u : kb;
+        pre.b0[u] = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
+        pre.b1[u] = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
+      }
+    }
+    if ((rd * NU + blockIdx.x * 2) < ph.items) df_prefetch_down(a, wdown, kt2, wd);
+    uint32_t dummy0, dummy1;
+    bool ok = true;
+    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1);
+    if (!ok) *sdead = 1;
+    __syncthreads();
+    if (*sdead) return true;
+    if (rd == 0) DF_STAMP(slot);
+    f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
+    const uint32_t* arow_p = As + arow * (ph.K + 4) + g * 8;
+    if (valid) {
+      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)item * KT * 64 + lane;
+      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)item * KT * 64 + lane;
+#pragma unroll
+      for (int u = 0; u < PF_K; ++u)
+        if (kb + u < ke) {
+          u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+          if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
+          mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
+        }
+      for (int kt = kb + PF_K; kt < ke; ++kt) {
+        u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+        if (arow < M) frag_from_lds(arow_p + kt * 32, xh, xl);
+        mfma_pair(xh, xl, __builtin_nontemporal_load(w0 + (size_t)kt * 64), __builtin_nontemporal_load(w1 + (size_t)kt * 64),
+                  acc0, acc1);
+      }
+    }
+    const int obase = (g * 4) * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      red[uw][0][obase + r * 16] = acc0[r];
+      red[uw][1][obase + r * 16] = acc1[r];
+    }
+    float sq = 0.f;
+    if (row < M)
+      for (int p = col; p < KT; p += 16) sq += sqs[row * KT + p];
+    __syncthreads();
+    float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
+    float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+    const float inv = 1.0f / sqrtf(sq / (float)ph.K + a.eps);
+    v0 *= inv;
+    v1 *= inv;
+    const float actv = (live && n0 < ph.N) ? v0 / (1.0f + expf(-v0)) * v1 : 0.f;
+    sact[row * 36 + usel * 16 + col] = split_payload(actv);          // [16 rows][32 columns of the workgroup's k-tile]
+    __syncthreads();
+    // ---- down projection of the workgroup's 32 columns: wave takes output tiles wave, wave + 8, ...
+    if ((rd * NU + blockIdx.x * 2) < ph.items) {
+      u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+      if (arow < M) frag_from_lds(sact + arow * 36 + g * 8, xh, xl);
+      const bf16x8 ah = __builtin_bit_cast(bf16x8, xh), al = __builtin_bit_cast(bf16x8, xl);
+      u64* po = part2 + ((size_t)kt2 * PR) * a.d;
+#pragma unroll
+      for (int i = 0; i < DF_DN; ++i) {
+        const int nt = wave + 8 * i;
+        if (nt < ntiles_d) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, wd.b[i]);
+          f32x4 acc = f32x4{0, 0, 0, 0};
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bv, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bv, acc, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (4 * g + r < M) st_wordf(po + (size_t)(4 * g + r) * a.d + nt * 16 + c16, acc[r], tag2);
+        }
+      }
+      for (int nt = wave + 8 * DF_DN; nt < ntiles_d; nt += 8) {      // wider models: the remaining tiles, not prefetched
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4*)wdown + ((size_t)nt * KTd + kt2) * 64 + lane));
+        f32x4 acc = f32x4{0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bv, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bv, acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (4 * g + r < M) st_wordf(po + (size_t)(4 * g + r) * a.d + nt * 16 + c16, acc[r], tag2);
+      }
+    }
+    if (rd == 0) DF_STAMP(slot + 1);
+    __syncthreads();
+  }
+  return false;
+}
+
+// Sum of the ffn/32 down-projection partials in ascending order, residual, and the operand / statistics of the next
+// RMSNorm.  Task = (row, 32 output columns); thread (column c, group g of 8) sums the partials of its group, the
+// groups meet in LDS in ascending order.
+constexpr int DF_RW = 20;                 // partials a thread keeps in flight
+__device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const u64* part2, uint32_t tag2, const u64* h_in,
+                                                u64* h_out, u64* hg_out, u64* sq_out, const float* gain_next, int shift,
+                                                uint32_t* lds, int* sdead, int slot) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), usel = wave >> 2, ut = tid & 255;
+  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  const int M = a.rows.M, d = a.d, np = d >> 5, nW = a.ffn >> 5, PR = (int)(a.st_h / a.d);
+  const int tasks = M * np, rounds = (tasks + NU - 1) / NU;
+  const int uitem = df_item_of_unit(unit, shift, NU);
+  float* rs = (float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048;      // [8 groups][32]
+  const int c = ut & 31, grp = ut >> 5;
+  const int per = (nW + 7) >> 3;
+  uint32_t* err = a.bar + 64;
+  bool bad = false;
+  for (int rd = 0; rd < rounds; ++rd) {
+    const int task = rd * NU + uitem;
+    const bool valid = task < tasks;
+    const int m = valid ? task / np : 0, p = valid ? task - m * np : 0;
+    const int w0 = grp * per, cnt = valid ? max(0, min(per, nW - w0)) : 0;
+    const u64* src = part2 + ((size_t)w0 * PR + m) * d + 32 * p + c;
+    const size_t wstride = (size_t)PR * d;
+    float sum = 0.f;
+    u64 hw = (u64)a.tag << 32;
+    const bool want_h = valid && grp == 0;
+    for (int b0 = 0; b0 < cnt || (b0 == 0 && want_h); b0 += DF_RW) {
+      u64 v[DF_RW];
+#pragma unroll
+      for (int i = 0; i < DF_RW; ++i) v[i] = (b0 + i < cnt) ? ld_word(src + (size_t)(b0 + i) * wstride) : ((u64)tag2 << 32);
+      if (b0 == 0 && want_h) hw = ld_word(h_in + (size_t)m * d + 32 * p + c);
+      long spins = 0;
+      for (;;) {
+        bool all = (uint32_t)(hw >> 32) == a.tag;
+#pragma unroll
+        for (int i = 0; i < DF_RW; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag2);
+        if (all) break;
+        if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
+          bad = true;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+        for (int i = 0; i < DF_RW; ++i)
+          if ((uint32_t)(v[i] >> 32) != tag2) v[i] = ld_word(src + (size_t)(b0 + i) * wstride);
+        if ((uint32_t)(hw >> 32) != a.tag) hw = ld_word(h_in + (size_t)m * d + 32 * p + c);
+      }
+#pragma unroll
+      for (int i = 0; i < DF_RW; ++i)
+        if (b0 + i < cnt) sum += __uint_as_float((uint32_t)v[i]);
+    }
+    rs[grp * 32 + c] = sum;
+    if (bad) *sdead = 1;
+    __syncthreads();
+    if (*sdead) return true;
+    if (rd == 0) DF_STAMP(slot);
+    if (valid && ut < 32) {
+      float v = rs[c];
+#pragma unroll
+      for (int gq = 1; gq < 8; ++gq) v += rs[gq * 32 + c];
+      v += __uint_as_float((uint32_t)hw);
+      const size_t o = (size_t)m * d + 32 * p + c;
+      st_wordf(h_out + o, v, a.tag);
+      st_word(hg_out + o, split_payload(v * gain_next[32 * p + c]), a.tag);
+      float q2 = v * v;
+#pragma unroll
+      for (int off = 16; off > 0; off >>= 1) q2 += __shfl_xor(q2, off, 32);
+      if (c == 0) st_wordf(sq_out + (size_t)m * np + p, q2, a.tag);
+    }
+    if (rd == 0) DF_STAMP(slot + 1);
+    __syncthreads();
+  }
+  (void)layer;
   return false;
 }
 
@@ -859,6 +1142,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
 __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[DF_LDS_WORDS];
   __shared__ int srow[3 * 16];
+  __shared__ uint32_t sact[16 * 36];
   __shared__ int sdead;
   if (threadIdx.x == 0) sdead = 0;
   const int nqkv = (a.nq + 2 * a.nkv) * 64, nqd = a.nq * 64, L = a.n_layers, np = a.d >> 5;
@@ -908,33 +1192,17 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int wave_k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int unit = blockIdx.x * 2 + (wave_k >> 2);
   auto has = [&](int u, int shift, int items) { return df_item_of_unit(u, shift, NU) < items; };
-  const bool u_q = has(unit, 0, n_qkv), u_o = has(unit, s_o, n_o), u_g = has(unit, 0, n_gu), u_d = has(unit, s_dn, n_dn),
+  const int n_red = a.rows.M * np, s_red = s_dn;
+  const bool u_q = has(unit, 0, n_qkv), u_o = has(unit, s_o, n_o), u_g = has(unit, 0, n_gu),
              u_l = a.with_head && has(unit, 0, n_lg);
   const int u0 = blockIdx.x * 2, u1 = u0 + 1;
   const bool g_q = has(u0, 0, n_qkv) || has(u1, 0, n_qkv), g_a = has(u0, s_att, n_att) || has(u1, s_att, n_att),
-             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = has(u0, 0, n_gu) || has(u1, 0, n_gu) || n_gu > NU,
-             g_d = has(u0, s_dn, n_dn) || has(u1, s_dn, n_dn), g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
+             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = has(u0, 0, n_gu) || n_gu > NU,
+             g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
 
-  WPre w;
-  int w_for = -1;                     // phase (5 * layer + kind; 5L: head) whose weights `w` holds
-  // Request the weights of the unit's first item at or after phase `from` (kinds 0 QKV, 2 O, 3 gate/up, 4 down).
-  auto prefetch_from = [&](int from) {
-    DPhase x = DPhase{};
-    int epi = -1, at = -1;
-    for (int ph = from; ph <= 5 * L && ph < from + 6 && epi < 0; ++ph) {
-      const int l = ph / 5, k = ph - l * 5;
-      at = ph;
-      if (ph == 5 * L) { if (u_l) { x = make_head(); epi = PE_LOGITS; } break; }
-      if (k == 0 && u_q) { x = make_qkv(l); epi = PE_QKV; }
-      else if (k == 2 && u_o) { x = make_resid(l, 0); epi = PE_RESID; }
-      else if (k == 3 && u_g) { x = make_swiglu(l); epi = PE_SWIGLU; }
-      else if (k == 4 && u_d) { x = make_resid(l, 1); epi = PE_RESID; }
-    }
-    if (epi >= 0) { df_prefetch(x, epi, w); w_for = at; }
-  };
+  WPre w;                             // unused placeholder of the phases' prefetch interface
 
   df_embed_phase(a);
-  prefetch_from(0);
   if (df_start_barrier(a, &sdead)) return;
   const DAttItem ait = df_att_item(a, df_item_of_unit(unit, s_att, NU), ntile, wave_k & 3, threadIdx.x & 63);
   if (threadIdx.x < a.rows.M) {                           // per-row constants of the launch: position, active, block of the new key
@@ -950,27 +1218,30 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     const int s0 = 2 + l * 10, p0 = 5 * l;
     if (g_q) {
       const DPhase cur = make_qkv(l);
-      if (df_gemm_phase<PE_QKV>(a, cur, w, w_for == p0, lds, srow, &sdead, s0, [&]() { if (w_for < p0 + 1) prefetch_from(p0 + 1); })) return;
+      if (df_gemm_phase<PE_QKV, 1, false>(a, cur, w, false, lds, srow, &sdead, s0, []() {})) return;
     }
     if (g_a) {
       if (df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
     }
     if (g_o) {
       const DPhase cur = make_resid(l, 0);
-      if (df_gemm_phase<PE_RESID>(a, cur, w, w_for == p0 + 2, lds, srow, &sdead, s0 + 4, [&]() { if (w_for < p0 + 3) prefetch_from(p0 + 3); })) return;
+      if (df_gemm_phase<PE_RESID, 1, true>(a, cur, w, false, lds, srow, &sdead, s0 + 4, []() {})) return;
     }
     if (g_g) {
       const DPhase cur = make_swiglu(l);
-      if (df_gemm_phase<PE_SWIGLU>(a, cur, w, w_for == p0 + 3, lds, srow, &sdead, s0 + 6, [&]() { if (w_for < p0 + 4) prefetch_from(p0 + 4); })) return;
+      u64* p2 = a.part2 + (size_t)(l & 1) * a.st_part2;
+      if (df_mlp_phase(a, cur, layer_ptrs(a, l).wdown, p2, df_tag2(a, l), lds, sact, &sdead, s0 + 6)) return;
     }
-    if (g_d) {
-      const DPhase cur = make_resid(l, 1);
-      if (df_gemm_phase<PE_RESID>(a, cur, w, w_for == p0 + 4, lds, srow, &sdead, s0 + 8, [&]() { if (w_for < p0 + 5) prefetch_from(p0 + 5); })) return;
+    if (g_r) {
+      const size_t hi = (size_t)(2 * l + 1);
+      const float* gain_next = l + 1 < L ? layer_ptrs(a, l + 1).ln1 : a.final_norm;
+      if (df_reduce_phase(a, l, a.part2 + (size_t)(l & 1) * a.st_part2, df_tag2(a, l), a.h + hi * a.st_h, a.h + (hi + 1) * a.st_h,
+                          a.hg + (hi + 1) * a.st_h, a.sq + (hi + 1) * a.st_sq, gain_next, s_red, lds, &sdead, s0 + 8)) return;
     }
   }
   if (a.with_head && g_l) {
     const DPhase cur = make_head();
-    df_gemm_phase<PE_LOGITS>(a, cur, w, w_for == 5 * L, lds, srow, &sdead, 2 + L * 10, []() {});
+    df_gemm_phase<PE_LOGITS, 1, false>(a, cur, w, false, lds, srow, &sdead, 2 + L * 10, []() {});
   }
 }
 

@@ -304,7 +304,7 @@ struct ssd_kv {
   uint32_t epoch = 0;
   int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
   // tagged workspace of the barrier-free forward (see dataflow.h); null when that kernel is not usable
-  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_act, *t_part, *t_att_p;
+  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_act, *t_part, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
   // host
@@ -358,13 +358,14 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   const size_t w_h = (size_t)(2 * L + 1) * TR * c.d_model, w_sq = (size_t)(2 * L + 1) * TR * (c.d_model / 32);
   const size_t w_q = (size_t)L * TR * nqd, w_kvn = (size_t)L * TR * 2 * c.n_kv_heads * 64, w_act = (size_t)L * TR * c.d_ffn;
   const size_t w_part = (size_t)2 * L * P_MAX_SPLITS * TR * c.d_model, w_attp = (size_t)L * TR * c.n_q_heads * NP * 96;
-  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_act + w_part + w_attp;
+  const size_t w_part2 = (size_t)2 * (c.d_ffn / 32) * TR * c.d_model;
+  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_act + w_part + w_attp + w_part2;
   u64* t_base = cv.take<u64>(t_words);
   if (kv) {
     u64* t = t_base;
     kv->t_base = t_base; kv->t_words = t_words;
     kv->t_h = t; t += w_h; kv->t_hg = t; t += w_h; kv->t_sq = t; t += w_sq; kv->t_q = t; t += w_q; kv->t_attn = t; t += w_q;
-    kv->t_kvn = t; t += w_kvn; kv->t_act = t; t += w_act; kv->t_part = t; t += w_part; kv->t_att_p = t;
+    kv->t_kvn = t; t += w_kvn; kv->t_act = t; t += w_act; kv->t_part = t; t += w_part; kv->t_att_p = t; t += w_attp; kv->t_part2 = t;
 
     kv->trace = trace;
     kv->p_h = p_h; kv->p_hg = p_hg; kv->p_sumsq = p_sumsq; kv->p_q = p_q; kv->p_attn = p_attn; kv->p_act = p_act; kv->p_part = p_part; kv->p_att_o = p_att_o;
@@ -577,10 +578,9 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   // query rows of an item, LDS staging capacity
   auto kn_max = [&](int K, int gs) { return cdiv(K / 32, gs) * 32; };
   const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU && npairs * gs_o <= NU &&
-                    npairs * gs_d <= NU && M * (c.d_model + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
+                    M * (c.d_model + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
                     (gs_o == 1 ? M * (nqd + 4) <= DF_AW : M * (kn_max(nqd, gs_o) + 4) <= DF_AW / 2) &&
-                    (gs_d == 1 ? M * (c.d_ffn + 4) <= DF_AW : M * (kn_max(c.d_ffn, gs_d) + 4) <= DF_AW / 2) &&
-                    2 + 10 * c.n_layers + 2 <= 512;
+                    c.n_layers <= 128 && 2 + 10 * c.n_layers + 2 <= 512;
   if (!fits) return -1;
   DArgs a;
   memset(&a, 0, sizeof a);
@@ -597,6 +597,7 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.st_h = PR * c.d_model; a.st_sq = PR * (c.d_model / 32); a.st_q = PR * nqd; a.st_kvn = PR * 2 * c.n_kv_heads * 64;
   a.st_act = PR * c.d_ffn; a.st_part = (size_t)P_MAX_SPLITS * PR * c.d_model; a.part_stride = PR * c.d_model;
   a.st_att_p = PR * c.n_q_heads * kv->NP * 96;
+  a.part2 = kv->t_part2; a.st_part2 = (size_t)(c.d_ffn / 32) * PR * c.d_model;
   a.NP = kv->NP; a.n_parts = n_parts; a.gs_o = gs_o; a.gs_d = gs_d;
   a.bar = kv->bar;
   a.tag = ++kv->epoch;
