@@ -126,7 +126,7 @@ def main():
     for i in range(20):
         verify_once(i)
     k_ms, k_n = ssd.ssd_profile_end()
-    kernel_name = "k_forward_persistent"
+    kernel_name = "k_forward_dataflow"          # the whole-forward kernel of the bf16 path (profile kind "persistent")
     fwd_bytes = abytes - (2 * K + 1) * tshape["vocab"] * 4 + (K + 1) * tshape["vocab"] * 4   # weights + KV + logits out
     if k_n == 0:                                    # shapes the persistent kernel does not cover: gate/up GEMM instead
         ssd.ssd_profile_begin("gate_up")

@@ -1,23 +1,29 @@
 // The decoder forward of one verification (Eq. 4) as one persistent kernel WITHOUT grid barriers between phases.
 //
-// Same decomposition as k_forward_persistent (five phases per layer, a unit of 4 waves per item, weights packed
-// as matrix-core fragments), but dependent phases are ordered by the data itself: everything a workgroup hands
-// to another workgroup is an 8-byte word {payload, tag}, stored with one agent-scope 64-bit store, where tag is
-// the number of this launch.  A consumer loads the words it needs with agent-scope 64-bit loads and repeats the
-// loads whose tag is not yet this launch's.  An aligned 8-byte store is observed whole, so a matching tag proves
-// the payload; no store has to be acknowledged before a flag is raised, no counter is shared, and the latency of a
-// dependency is one store plus one load instead of the five memory round trips of a barrier.
+// Phases per layer: QKV (+bias, rotary, cache append) -> attention (parts of 256 keys, then the merge of the parts)
+// -> output projection (+residual) -> MLP (gate/up + SwiGLU + down projection fused inside a workgroup) -> sum of the
+// MLP partials (+residual).  Weights are packed as matrix-core fragments; a unit of 4 waves takes an item.
 //
-// Every word is written exactly once per launch (each layer and phase has its own buffers), and launches that use
-// the same cache workspace are ordered by the stream, so a tag can never be matched by an older value.
+// Dependent phases are ordered by the data itself: everything a workgroup hands to another workgroup is an 8-byte
+// word {payload, tag}, stored with one agent-scope 64-bit store, where tag is the number of this launch.  A consumer
+// loads the words it needs with agent-scope 64-bit loads and repeats the loads whose tag is not yet this launch's.
+// An aligned 8-byte store is observed whole, so a matching tag proves the payload; no store has to be acknowledged
+// before a flag is raised, no counter is shared, and a dependency costs one store plus one load instead of the
+// chain of memory round trips of a barrier.  Every word is written exactly once per launch (each layer and phase
+// has its own buffers; the MLP partials alternate between two buffers and carry the layer in their tag), and
+// launches on one cache workspace are ordered by the stream, so a tag cannot be matched by an older value.
 //
 // Payloads: a GEMM operand value x is hi | lo << 16 with hi = upper 16 bits of x and lo = bf16(x - hi) (the two
-// bf16 whose sum the matrix core consumes); residual rows, sums of squares and partial results are fp32 bits;
-// new keys / values are bf16 bits.
+// bf16 whose sum the matrix core consumes); residual rows, sums of squares and partial results are fp32 bits; new
+// keys / values are bf16 bits.
 //
-// A workgroup stages the operand rows it needs in LDS once (all its waves poll in parallel, 12 words in flight per
-// thread), then feeds the matrix cores from LDS.  Weights of the following phase are requested as soon as the
-// operands of the current phase have arrived, so their HBM latency overlaps the current phase and the hand-over.
+// A workgroup stages the operand rows it needs in LDS once (all its threads poll in parallel, 14 words in flight
+// each) and feeds the matrix cores from LDS.  The weights of an item are requested at the entry of its phase, into
+// registers, before that wait: workgroups arrive at a phase before its operands do, so the wait hides the HBM latency.
+// The phases with few items (QKV, attention, output projection) run on workgroups of their own, beyond those that
+// take the MLP items, so that no workgroup is late for the MLP, the phase every workgroup waits for.
+// Polling costs fabric bandwidth that the producers' stores need: a wave whose first flight fails first watches a
+// single word of the PRECEDING phase's operands with long sleeps, and polls in earnest only from then on.
 //
 // Attention never reads this launch's new keys from the cache pool: the QKV phase stores them in the pool for
 // later launches and, tagged, in a side buffer; a wave whose 64-key chunk reaches the new positions patches its
@@ -44,13 +50,6 @@ constexpr int DF_ATT_UNIT = 4096 + 512 + 512 + 4096 + 4096 + 128;      // Q | ne
 constexpr int DF_LDS_WORDS = (DF_AW + DF_SQ_WORDS + DF_RED_WORDS) > 2 * DF_ATT_UNIT ? (DF_AW + DF_SQ_WORDS + DF_RED_WORDS)
                                                                                   : 2 * DF_ATT_UNIT;
 
-#ifndef DF_QKV_LOCAL
-#define DF_QKV_LOCAL 0          // 1: the QKV phase keeps its weights in registers of its own; 0: in the shared prefetch buffer
-#endif
-#ifndef DF_O_MODE
-#define DF_O_MODE 0             // 0: output projection weights in the shared prefetch buffer; 2: L2 warm-up + in-phase loads
-#endif
-
 struct DArgs {
   int n_layers, d, nq, nkv, ffn, vocab, n_embed;
   float eps, scale;
@@ -72,15 +71,14 @@ struct DArgs {
   u64* q;                 // [L][PR][nq*64]     operand: rotated queries
   u64* kvn;               // [L][PR][2][nkv*64] bf16: this launch's keys (rotated) and values
   u64* attn;              // [L][PR][nq*64]     operand: attention output
-  u64* act;               // [L][PR][ffn]       operand: SwiGLU output
-  u64* part;              // [2L][P_MAX_SPLITS][PR][d] fp32: k-split partials (splits >= 1) of the output / down projections
   u64* att_p;             // [L][PR][nq][NP][16][6] fp32: per part and 4-dim chunk: 4 weighted values, max, sum
   u64* part2;             // [2][ffn/32][PR][d] fp32: down-projection partials of one 32-column slice of the SwiGLU output each,
                           // tagged with launch and layer (buffer = layer parity)
   size_t st_part2;
   float* logits;
-  size_t st_h, st_sq, st_q, st_kvn, st_act, st_part, st_att_p, part_stride;   // strides in words
-  int NP, n_parts, gs_o, gs_d;
+  size_t st_h, st_sq, st_q, st_kvn, st_att_p;   // strides in words
+  int NP, n_parts;
+  int g_mlp;              // workgroups [0, g_mlp) take the MLP items; the phases with few items start on the workgroups after them
   uint32_t* bar;          // [0] arrivals, [32] flag, [64] error flag
   unsigned long long* trace;
 };
@@ -95,10 +93,23 @@ __device__ __forceinline__ uint32_t split_payload(float x) {
   return (h >> 16) | ((uint32_t)f_to_bf16(x - __uint_as_float(h)) << 16);
 }
 
+// A workgroup that arrives at a phase long before its operands would poll them the whole time, and the polls of all
+// such workgroups load the fabric that the producers' stores travel through.  After a first failed flight a wave
+// therefore watches one word of the operands of the PRECEDING phase (one hand-over earlier) with a single
+// address and long sleeps, and resumes the full polling when that word is there.  Purely a hint: bounded, and
+// nothing depends on what it saw.
+__device__ __forceinline__ void df_wait_hint(const u64* word, uint32_t tag, uint32_t* err) {
+  for (int i = 0; i < (1 << 14); ++i) {
+    if ((uint32_t)(ld_word(word) >> 32) == tag) return;
+    if ((i & 63) == 63 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0) return;
+    __builtin_amdgcn_s_sleep(16);
+  }
+}
+
 // Loads the words base[off[i]] (off == ~0: none) until every tag is this launch's.  False on a timeout.
 template <int N>
 __device__ __forceinline__ bool poll_words(const u64* base, const uint32_t (&off)[N], uint32_t tag, uint32_t (&out)[N],
-                                           uint32_t* err) {
+                                           uint32_t* err, const u64* hint = nullptr, uint32_t hint_tag = 0u) {
   u64 v[N];
 #pragma unroll
   for (int i = 0; i < N; ++i) v[i] = off[i] != 0xFFFFFFFFu ? ld_word(base + off[i]) : ((u64)tag << 32);
@@ -109,6 +120,7 @@ __device__ __forceinline__ bool poll_words(const u64* base, const uint32_t (&off
 #pragma unroll
     for (int i = 0; i < N; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag);
     if (all) break;
+    if (spins == 0 && hint) df_wait_hint(hint, hint_tag, err);
     if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
       __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
       ok = false;
@@ -158,17 +170,18 @@ struct DPhase {
   const u64* sq;          // [PR][K/32] sums of squares of the un-gained rows (nullptr: no RMSNorm)
   const void* W0;
   const void* W1;
-  int N, K, gs, items;
+  int N, K, gs, items;    // gs: k-splits, always 1 here (the field the shared k-range helper reads)
   int shift;              // item i of round 0 runs on unit (i + shift) % units
+  const u64* hint;        // a word of the preceding phase's operands (see df_wait_hint), or null
+  uint32_t hint_tag;
   int layer;
   const float* bias;
-  const u64* h_in;        // PE_RESID
+  const u64* h_in;        // PE_RESID: residual input and outputs
   u64* h_out;
   u64* hg_out;
   u64* sq_out;
   const float* gain_next;
-  u64* part;
-  u64* out;               // PE_QKV: q; PE_SWIGLU: act
+  u64* out;               // PE_QKV: q
   u64* kvn;               // PE_QKV: side buffer of the new keys / values
   float* logits;          // PE_LOGITS
 };
@@ -179,7 +192,7 @@ struct DPhase {
 // load instead of being kept in registers.
 __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, int k0, int kn, const u64* sq, int KT,
                                               uint32_t* As, float* sqs, int gt, int gn, uint32_t x0, uint32_t x1,
-                                              uint32_t& xo0, uint32_t& xo1) {
+                                              uint32_t& xo0, uint32_t& xo1, const u64* hint, uint32_t hint_tag) {
   const int M = a.rows.M, nA = M * kn, total = nA + (sq ? M * KT : 0), stride = kn + 4;
   const uint32_t a_off = (uint32_t)(A - a.tw), s_off = sq ? (uint32_t)(sq - a.tw) : 0u;
   const float rkn = 1.0f / (float)kn;
@@ -209,6 +222,7 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
 #pragma unroll
       for (int u = 0; u < DF_B + 2; ++u) all = all && ((uint32_t)(v[u] >> 32) == tag);
       if (all) break;
+      if (spins == 0 && hint) df_wait_hint(hint, hint_tag, err);       // far too early: wait cheaply for the phase before
       if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
         __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
         ok = false;
@@ -256,44 +270,13 @@ __device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU) {
   return i < 0 ? i + NU : i;
 }
 
-// Weight fragments of the unit's round-0 item of phase `ph` (epilogue kind epi), as prefetch_weights does, with the
-// kind and the unit -> item shift taken at run time.  Does nothing when the unit has no item in that phase.
-__device__ __forceinline__ void df_prefetch(const DPhase& ph, int epi, WPre& pre) {
-  int tid = threadIdx.x;
-  asm volatile("" : "+v"(tid));
-  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int unit = blockIdx.x * 2 + (wave >> 2), NU = gridDim.x * 2;
-  const int item = df_item_of_unit(unit, ph.shift, NU);
-  if (item >= ph.items) return;
-  int t0, t1, split = 0;
-  if (epi == PE_QKV) { t0 = (item >> 1) * 4 + (item & 1); t1 = t0 + 2; }
-  else if (epi == PE_SWIGLU) { t0 = item; t1 = item; }
-  else {
-    const int npairs = (((ph.N + 15) >> 4) + 1) >> 1;
-    split = item / npairs;
-    const int p = item - split * npairs;
-    t0 = 2 * p; t1 = 2 * p + 1;
-  }
-  int kb, ke;
-  wave_krange(ph, split, wave & 3, kb, ke);
-  const int KT = ph.K >> 5, ntiles = (ph.N + 15) >> 4;
-  const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
-  const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(t1 < ntiles ? t1 : t0) * KT * 64 + lane;
-#pragma unroll
-  for (int u = 0; u < PF_K; ++u) {
-    const int kt = (kb + u < ke) ? kb + u : kb;
-    pre.b0[u] = __builtin_nontemporal_load(w0 + (size_t)kt * 64);
-    pre.b1[u] = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
-  }
-}
-
-// One GEMM phase; the caller skips it for a workgroup none of whose units has an item.  When `pre_ok`, `pre` holds the
-// weight fragments of the unit's round-0 item (requested one or more phases earlier).  `after` is called once the
-// products of round 0 are issued and `pre` is free again (for the unit that sums the splits: after its wait for them).
+// One GEMM phase (QKV, output projection, head); the caller skips it for a workgroup none of whose units has an
+// item.  The weight fragments of the unit's item are requested at entry, into registers, before the wait for the
+// operands: units arrive well before their operands do, so the weights' HBM latency is hidden by that wait.
 // Returns true if the workgroup has to leave (timeout somewhere in the grid).
-template <int EPI, int LOCALW, bool SPLITS, typename FAfter>
-__device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, const WPre& pre, bool pre_ok, uint32_t* lds,
-                                              const int* srow, int* sdead, int slot, FAfter&& after) {
+template <int EPI>
+__device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, uint32_t* lds, const int* srow, int* sdead,
+                                              int slot) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -308,33 +291,19 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
   const int arow = lane & 15, g = lane >> 4;
   const int row = ut >> 4, col = ut & 15;
   const int rounds = (ph.items + NU - 1) / NU;
-  const bool shared = ph.gs == 1;                      // both units of the workgroup consume the same operand rows
   for (int rd = 0; rd < rounds; ++rd) {
     DF_FINE(0);
     const int item = rd * NU + uitem;
     int t0, t1, split, kb = 0, ke = 0;
     const bool valid = gemm_item<EPI>(ph, item, t0, t1, split);
-    if (valid) wave_krange(ph, split, uw, kb, ke);
+    if (valid) wave_krange(ph, 0, uw, kb, ke);
     const bool has1 = t1 < ntiles;
     const bool live = valid && row < M;
-    const bool reducer = EPI == PE_RESID && valid && split == 0;
     const int n0 = t0 * 16 + col, n1 = t1 * 16 + col;
-    // A phase with few items (LOCALW) requests its weights here, into registers of its own: its units arrive long
-    // before their operands do, and `pre` keeps the weights of the unit's next large phase.
+    const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
+    const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
     WPre wl;
-    uint32_t warm0 = 0u, warm1 = 0u;
-    if (LOCALW == 2 && rd == 0 && valid) {
-      // one dword of each 128-byte line of the wave's weight fragments: brings them into this XCD's L2 while the
-      // unit waits for its operands; the real loads after that wait are L2 hits
-      const char* b0 = (const char*)ph.W0 + ((size_t)t0 * KT + kb) * 1024;
-      const char* b1 = (const char*)ph.W1 + ((size_t)(has1 ? t1 : t0) * KT + kb) * 1024;
-      const int nl = (ke - kb) * 8;                                  // lines per tile
-      if (lane < nl) warm0 = *(const volatile uint32_t*)(b0 + lane * 128);
-      if (lane < nl) warm1 = *(const volatile uint32_t*)(b1 + lane * 128);
-    }
-    if (LOCALW == 1 && rd == 0 && valid) {
-      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
-      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
+    if (valid) {
 #pragma unroll
       for (int u = 0; u < PF_K; ++u) {
         const int kt = (kb + u < ke) ? kb + u : kb;
@@ -342,30 +311,20 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
         wl.b1[u] = __builtin_nontemporal_load(w1 + (size_t)kt * 64);
       }
     }
-    // ---- operands; the unit that finishes the rows takes its residual inputs in the same flight
+    // ---- operands (both units of the workgroup consume the same rows); the unit that finishes residual rows takes
+    //      its residual inputs in the same flight
     uint32_t hx0 = 0xFFFFFFFFu, hx1 = 0xFFFFFFFFu, hv0 = 0u, hv1 = 0u;
-    if (reducer && row < M) {
+    if (EPI == PE_RESID && live) {
       const uint32_t h_off = (uint32_t)(ph.h_in - a.tw) + (uint32_t)(row * ph.N);
       hx0 = h_off + n0;
       hx1 = h_off + n1;
     }
-    int k0 = 0, kn = ph.K;
-    const uint32_t* Au = As;
     bool ok = true;
-    if (shared) {
-      if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1);
-    } else {
-      const int per_s = KT / ph.gs, rem_s = KT - per_s * ph.gs;
-      k0 = (split * per_s + min(split, rem_s)) * 32;
-      kn = (per_s + (split < rem_s ? 1 : 0)) * 32;
-      Au = As + usel * (DF_AW / 2);
-      if (valid) ok = stage_operand(a, ph.A, ph.K, k0, kn, nullptr, 0, (uint32_t*)Au, sqs, ut, 256, hx0, hx1, hv0, hv1);
-    }
+    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
-    // ---- epilogue operands that do not depend on the product: requested before the weights of a later phase, so
-    //      that the epilogue never waits behind those (vector memory operations of a wave return in order)
+    // ---- epilogue operands that do not depend on the product
     float bias0 = 0.f, bias1 = 0.f, gn0 = 0.f, gn1 = 0.f;
     float2 cs = float2{1.f, 0.f};
     int pos = 0, active = 0, rblk = -1;
@@ -379,32 +338,16 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     DF_FINE(1);
     // ---- products
     f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
-    const int stride = kn + 4;
-    const uint32_t* arow_p = Au + arow * stride + g * 8 - k0;
+    const uint32_t* arow_p = As + arow * (ph.K + 4) + g * 8;
     if (valid) {
-      const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)t0 * KT * 64 + lane;
-      const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)(has1 ? t1 : t0) * KT * 64 + lane;
-      if (LOCALW == 2) asm volatile("" :: "v"(warm0), "v"(warm1));
-      if (rd == 0 && (LOCALW == 1 || pre_ok)) {
 #pragma unroll
-        for (int u = 0; u < PF_K; ++u)
-          if (kb + u < ke) {
-            u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
-            if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
-            if (LOCALW == 1) mfma_pair(xh, xl, wl.b0[u], wl.b1[u], acc0, acc1);
-            else mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
-          }
-      } else {
-#pragma unroll
-        for (int u = 0; u < PF_K; ++u)
-          if (kb + u < ke) {
-            u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
-            if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
-            mfma_pair(xh, xl, __builtin_nontemporal_load(w0 + (size_t)(kb + u) * 64),
-                      __builtin_nontemporal_load(w1 + (size_t)(kb + u) * 64), acc0, acc1);
-          }
-      }
-      for (int kt = kb + PF_K; kt < ke; ++kt) {
+      for (int u = 0; u < PF_K; ++u)
+        if (kb + u < ke) {
+          u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
+          if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
+          mfma_pair(xh, xl, wl.b0[u], wl.b1[u], acc0, acc1);
+        }
+      for (int kt = kb + PF_K; kt < ke; ++kt) {                       // waves with more than PF_K k-tiles
         u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
         if (arow < M) frag_from_lds(arow_p + kt * 32, xh, xl);
         mfma_pair(xh, xl, __builtin_nontemporal_load(w0 + (size_t)kt * 64), __builtin_nontemporal_load(w1 + (size_t)kt * 64),
@@ -462,45 +405,18 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
           }
         }
       }
-    } else if (EPI == PE_SWIGLU) {
-      if (live && n0 < ph.N) st_word(ph.out + (size_t)row * ph.N + n0, split_payload(v0 / (1.0f + expf(-v0)) * v1), a.tag);
     } else if (EPI == PE_LOGITS) {
       if (live) {
         if (n0 < ph.N) ph.logits[(size_t)row * ph.N + n0] = v0;
         if (has1 && n1 < ph.N) ph.logits[(size_t)row * ph.N + n1] = v1;
       }
-    } else {  // PE_RESID: the unit of split 0 sums the splits in ascending order and adds the residual
-      const int pair = t0 >> 1;
-      if (valid && split != 0) {
-        if (row < M) {
-          u64* o = ph.part + (size_t)split * a.part_stride + (size_t)row * ph.N;
-          st_wordf(o + n0, v0, a.tag);
-          st_wordf(o + n1, v1, a.tag);
-        }
-      } else if (valid) {
+    } else {  // PE_RESID: N == d (a multiple of 32): residual, and the operand / statistics of the next RMSNorm
+      if (valid) {
+        const int pair = t0 >> 1;
         float q2 = 0.f;
         if (row < M) {
-          constexpr int NW = 2 * (P_MAX_SPLITS - 1) + 2;
-          uint32_t off[NW], out[NW];
-          const uint32_t p_off = (uint32_t)(ph.part - a.tw) + (uint32_t)(row * ph.N);
-#pragma unroll
-          for (int s = 1; s < P_MAX_SPLITS; ++s) {
-            const bool use = s < ph.gs;
-            off[2 * (s - 1)] = use ? p_off + (uint32_t)(s * a.part_stride) + n0 : 0xFFFFFFFFu;
-            off[2 * (s - 1) + 1] = use ? p_off + (uint32_t)(s * a.part_stride) + n1 : 0xFFFFFFFFu;
-          }
-          off[NW - 2] = 0xFFFFFFFFu;
-          off[NW - 1] = 0xFFFFFFFFu;
-          if (SPLITS && ph.gs > 1) {
-            if (!poll_words<NW>(a.tw, off, a.tag, out, a.bar + 64)) *sdead = 1;
-          }
-          out[NW - 2] = hv0;
-          out[NW - 1] = hv1;
-#pragma unroll
-          for (int s = 1; s < P_MAX_SPLITS; ++s)
-            if (SPLITS && s < ph.gs) { v0 += __uint_as_float(out[2 * (s - 1)]); v1 += __uint_as_float(out[2 * (s - 1) + 1]); }
-          v0 += __uint_as_float(out[NW - 2]);
-          v1 += __uint_as_float(out[NW - 1]);
+          v0 += __uint_as_float(hv0);
+          v1 += __uint_as_float(hv1);
           st_wordf(ph.h_out + (size_t)row * ph.N + n0, v0, a.tag);
           st_wordf(ph.h_out + (size_t)row * ph.N + n1, v1, a.tag);
           st_word(ph.hg_out + (size_t)row * ph.N + n0, split_payload(v0 * gn0), a.tag);
@@ -514,15 +430,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     }
     if (rd == 0) DF_STAMP(slot + 1);
     DF_FINE(5);
-    if (rd == 0) {                       // the stores of this phase are on their way: now the weights of a later phase
-      __builtin_amdgcn_sched_barrier(0);
-      after();
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    DF_FINE(3);
     __syncthreads();
-    if (*sdead) return true;
-    DF_FINE(6);
   }
   return false;
 }
@@ -556,7 +464,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int usel = wave >> 2, uw = wave & 3, ut = tid & 255;
-  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  const int unit = blockIdx.x * 2 + usel, NU = a.g_mlp * 2;
   uint32_t* As = lds;
   float* sqs = (float*)(lds + DF_AW);
   float (*red)[2][256] = (float (*)[2][256])((float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048);
@@ -590,7 +498,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     if ((rd * NU + blockIdx.x * 2) < ph.items) df_prefetch_down(a, wdown, kt2, wd);
     uint32_t dummy0, dummy1;
     bool ok = true;
-    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1);
+    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -709,6 +617,7 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 #pragma unroll
         for (int i = 0; i < DF_RW; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag2);
         if (all) break;
+        if (spins == 0) df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, a.tag, err);
         if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
           __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
           bad = true;
@@ -745,7 +654,6 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
     if (rd == 0) DF_STAMP(slot + 1);
     __syncthreads();
   }
-  (void)layer;
   return false;
 }
 
@@ -949,7 +857,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
       }
     }
-    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64);
+    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64, a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
 #pragma unroll
     for (int u = 0; u < DF_B; ++u) {
       const int idx = u * 256 + ut;
@@ -1149,29 +1057,29 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int NU = gridDim.x * 2;
   // items of every phase kind, and the unit that takes item 0 (the kinds with few items go to different workgroups)
   const int n_qkv = (a.nq + 2 * a.nkv) * 2, ntile = (a.rows.R * (a.nq / a.nkv) + 15) >> 4,
-            n_att = a.n_seqs * a.nkv * a.n_parts * ntile, n_o = np * a.gs_o, n_gu = a.ffn >> 4,
-            n_dn = np * a.gs_d, n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
-  const int s_att = n_qkv % NU, s_o = (n_qkv + n_att) % NU, s_dn = (n_qkv + n_att + n_o) % NU;
+            n_att = a.n_seqs * a.nkv * a.n_parts * ntile, n_o = np, n_gu = a.ffn >> 4,
+            n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
+  const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + n_qkv) % NU, s_o = (s_att + n_att) % NU;
   auto make_qkv = [&](int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
-    x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = 0;
+    x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = s_qkv;
     x.bias = Y.bqkv; x.out = a.q + (size_t)l * a.st_q; x.kvn = a.kvn + (size_t)l * a.st_kvn;
+    if (l > 0) { x.hint = a.part2 + (size_t)((l - 1) & 1) * a.st_part2; x.hint_tag = df_tag2(a, l - 1); }
     return x;
   };
-  auto make_resid = [&](int l, int second) {
+  auto make_o = [&](int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l;
-    x.A = second ? a.act + (size_t)l * a.st_act : a.attn + (size_t)l * a.st_q;
-    x.W0 = second ? Y.wdown : Y.wo; x.W1 = x.W0; x.N = a.d; x.K = second ? a.ffn : nqd;
-    x.gs = second ? a.gs_d : a.gs_o; x.items = np * x.gs; x.shift = second ? s_dn : s_o;
-    const size_t hi = (size_t)(2 * l + second);
+    x.A = a.attn + (size_t)l * a.st_q;
+    x.W0 = Y.wo; x.W1 = Y.wo; x.N = a.d; x.K = nqd; x.gs = 1; x.items = n_o; x.shift = s_o;
+    const size_t hi = (size_t)(2 * l);
     x.h_in = a.h + hi * a.st_h; x.h_out = a.h + (hi + 1) * a.st_h; x.hg_out = a.hg + (hi + 1) * a.st_h;
     x.sq_out = a.sq + (hi + 1) * a.st_sq;
-    x.gain_next = second ? (l + 1 < L ? layer_ptrs(a, l + 1).ln1 : a.final_norm) : Y.ln2;
-    x.part = a.part + hi * a.st_part;
+    x.gain_next = Y.ln2;
+    x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = a.tag;
     return x;
   };
   auto make_swiglu = [&](int l) {
@@ -1179,7 +1087,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
     x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0;
-    x.out = a.act + (size_t)l * a.st_act;
+    x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag;
     return x;
   };
   auto make_head = [&]() {
@@ -1192,15 +1100,11 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int wave_k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int unit = blockIdx.x * 2 + (wave_k >> 2);
   auto has = [&](int u, int shift, int items) { return df_item_of_unit(u, shift, NU) < items; };
-  const int n_red = a.rows.M * np, s_red = s_dn;
-  const bool u_q = has(unit, 0, n_qkv), u_o = has(unit, s_o, n_o), u_g = has(unit, 0, n_gu),
-             u_l = a.with_head && has(unit, 0, n_lg);
+  const int n_red = a.rows.M * np, s_red = s_qkv;
   const int u0 = blockIdx.x * 2, u1 = u0 + 1;
-  const bool g_q = has(u0, 0, n_qkv) || has(u1, 0, n_qkv), g_a = has(u0, s_att, n_att) || has(u1, s_att, n_att),
-             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = has(u0, 0, n_gu) || n_gu > NU,
+  const bool g_q = has(u0, s_qkv, n_qkv) || has(u1, s_qkv, n_qkv) || n_qkv > NU, g_a = has(u0, s_att, n_att) || has(u1, s_att, n_att),
+             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = (int)blockIdx.x < a.g_mlp,
              g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
-
-  WPre w;                             // unused placeholder of the phases' prefetch interface
 
   df_embed_phase(a);
   if (df_start_barrier(a, &sdead)) return;
@@ -1215,17 +1119,17 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   __syncthreads();
   DF_STAMP(0);
   for (int l = 0; l < L; ++l) {
-    const int s0 = 2 + l * 10, p0 = 5 * l;
+    const int s0 = 2 + l * 10;
     if (g_q) {
       const DPhase cur = make_qkv(l);
-      if (df_gemm_phase<PE_QKV, 1, false>(a, cur, w, false, lds, srow, &sdead, s0, []() {})) return;
+      if (df_gemm_phase<PE_QKV>(a, cur, lds, srow, &sdead, s0)) return;
     }
     if (g_a) {
       if (df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
     }
     if (g_o) {
-      const DPhase cur = make_resid(l, 0);
-      if (df_gemm_phase<PE_RESID, 1, true>(a, cur, w, false, lds, srow, &sdead, s0 + 4, []() {})) return;
+      const DPhase cur = make_o(l);
+      if (df_gemm_phase<PE_RESID>(a, cur, lds, srow, &sdead, s0 + 4)) return;
     }
     if (g_g) {
       const DPhase cur = make_swiglu(l);
@@ -1241,7 +1145,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   }
   if (a.with_head && g_l) {
     const DPhase cur = make_head();
-    df_gemm_phase<PE_LOGITS, 1, false>(a, cur, w, false, lds, srow, &sdead, 2 + L * 10, []() {});
+    df_gemm_phase<PE_LOGITS>(a, cur, lds, srow, &sdead, 2 + L * 10);
   }
 }
 

@@ -303,8 +303,9 @@ struct ssd_kv {
   int NP, p_rows;
   uint32_t epoch = 0;
   int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
+  int cus = 0;                     // compute units of the device
   // tagged workspace of the barrier-free forward (see dataflow.h); null when that kernel is not usable
-  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_act, *t_part, *t_att_p, *t_part2;
+  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
   // host
@@ -356,16 +357,16 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   // tagged words of the barrier-free forward: one block, zeroed at creation
   const size_t TR = PR;
   const size_t w_h = (size_t)(2 * L + 1) * TR * c.d_model, w_sq = (size_t)(2 * L + 1) * TR * (c.d_model / 32);
-  const size_t w_q = (size_t)L * TR * nqd, w_kvn = (size_t)L * TR * 2 * c.n_kv_heads * 64, w_act = (size_t)L * TR * c.d_ffn;
-  const size_t w_part = (size_t)2 * L * P_MAX_SPLITS * TR * c.d_model, w_attp = (size_t)L * TR * c.n_q_heads * NP * 96;
+  const size_t w_q = (size_t)L * TR * nqd, w_kvn = (size_t)L * TR * 2 * c.n_kv_heads * 64;
+  const size_t w_attp = (size_t)L * TR * c.n_q_heads * NP * 96;
   const size_t w_part2 = (size_t)2 * (c.d_ffn / 32) * TR * c.d_model;
-  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_act + w_part + w_attp + w_part2;
+  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_attp + w_part2;
   u64* t_base = cv.take<u64>(t_words);
   if (kv) {
     u64* t = t_base;
     kv->t_base = t_base; kv->t_words = t_words;
     kv->t_h = t; t += w_h; kv->t_hg = t; t += w_h; kv->t_sq = t; t += w_sq; kv->t_q = t; t += w_q; kv->t_attn = t; t += w_q;
-    kv->t_kvn = t; t += w_kvn; kv->t_act = t; t += w_act; kv->t_part = t; t += w_part; kv->t_att_p = t; t += w_attp; kv->t_part2 = t;
+    kv->t_kvn = t; t += w_kvn; kv->t_att_p = t; t += w_attp; kv->t_part2 = t;
 
     kv->trace = trace;
     kv->p_h = p_h; kv->p_hg = p_hg; kv->p_sumsq = p_sumsq; kv->p_q = p_q; kv->p_attn = p_attn; kv->p_act = p_act; kv->p_part = p_part; kv->p_att_o = p_att_o;
@@ -440,6 +441,7 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
       int want = std::max(32, cdiv(m->c.d_ffn / 16, 2));            // two gate/up tile pairs per workgroup
       if (const char* env = getenv("SSD_PERSISTENT_WGS")) want = atoi(env);
       kv->persistent_wgs = std::max(0, std::min(want, cus));        // one workgroup per CU at most: all co-resident
+      kv->cus = cus;
     }
   }
   // The barrier-free forward additionally needs its word offsets to fit 32 bits; its words start untagged (zero).
@@ -567,19 +569,20 @@ static int forward_persistent(const ssd_model* m, ssd_kv* kv, Rows rows, int B, 
 static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, int pcap, const int32_t* dev_tokens,
                             int tok_stride, bool with_head, hipStream_t st) {
   const ssd_model_config& c = m->c;
-  const int G = kv->persistent_wgs, NU = 2 * G, npairs = c.d_model / 32, M = rows.M;
+  const int npairs = c.d_model / 32, M = rows.M;
   const int nqd = c.n_q_heads * c.head_dim, grp = c.n_q_heads / c.n_kv_heads;
-  auto splits = [&](int K) { return std::max(1, std::min(std::min(NU / npairs, (K / 32) / 4), P_MAX_SPLITS)); };
-  const int gs_o = nqd / 32 <= 4 * PF_K ? 1 : splits(nqd), gs_d = splits(c.d_ffn);
   int max_len = 0;
   for (int s = rows.seq0; s < rows.seq0 + B; ++s) max_len = std::max(max_len, kv->len_ub[s]);
   const int n_parts = std::min(kv->NP, cdiv(max_len + rows.R, ATT_PART));
-  // limits: one round of attention and of the k-split projections (a unit that reduces must not wait for itself),
-  // query rows of an item, LDS staging capacity
-  auto kn_max = [&](int K, int gs) { return cdiv(K / 32, gs) * 32; };
-  const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU && npairs * gs_o <= NU &&
-                    M * (c.d_model + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
-                    (gs_o == 1 ? M * (nqd + 4) <= DF_AW : M * (kn_max(nqd, gs_o) + 4) <= DF_AW / 2) &&
+  // Workgroups [0, g_mlp) take the MLP items (two 16-column items each); the phases with few items (QKV, attention,
+  // output projection) get workgroups of their own after them, as far as the device has compute units.
+  const int g_mlp = std::min(kv->persistent_wgs, cdiv(c.d_ffn / 16, 2));
+  const int n_small = (c.n_q_heads + 2 * c.n_kv_heads) * 2 + B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) + npairs;
+  const char* ex = getenv("SSD_DF_EXTRA");
+  const int G = (ex && ex[0] == '0') ? g_mlp : std::min(kv->cus, g_mlp + cdiv(n_small, 2)), NU = 2 * G;
+  // limits: one round of attention (its units wait for each other's parts), query rows of an item, LDS staging capacity
+  const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU &&
+                    M * (c.d_model + 4) <= DF_AW && M * (nqd + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
                     c.n_layers <= 128 && 2 + 10 * c.n_layers + 2 <= 512;
   if (!fits) return -1;
   DArgs a;
@@ -593,12 +596,11 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.tokens = dev_tokens;
   const size_t PR = kv->p_rows;
   a.tw = kv->t_base; a.h = kv->t_h; a.hg = kv->t_hg; a.sq = kv->t_sq; a.q = kv->t_q; a.kvn = kv->t_kvn; a.attn = kv->t_attn;
-  a.act = kv->t_act; a.part = kv->t_part; a.att_p = kv->t_att_p; a.logits = kv->logits;
+  a.att_p = kv->t_att_p; a.logits = kv->logits;
   a.st_h = PR * c.d_model; a.st_sq = PR * (c.d_model / 32); a.st_q = PR * nqd; a.st_kvn = PR * 2 * c.n_kv_heads * 64;
-  a.st_act = PR * c.d_ffn; a.st_part = (size_t)P_MAX_SPLITS * PR * c.d_model; a.part_stride = PR * c.d_model;
   a.st_att_p = PR * c.n_q_heads * kv->NP * 96;
   a.part2 = kv->t_part2; a.st_part2 = (size_t)(c.d_ffn / 32) * PR * c.d_model;
-  a.NP = kv->NP; a.n_parts = n_parts; a.gs_o = gs_o; a.gs_d = gs_d;
+  a.NP = kv->NP; a.n_parts = n_parts; a.g_mlp = g_mlp;
   a.bar = kv->bar;
   a.tag = ++kv->epoch;
   a.trace = kv->trace_on ? kv->trace : nullptr;
@@ -943,7 +945,7 @@ extern "C" int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned
   if (!kv) return fail(SSD_EINVAL, "null handle");
   if (out) {
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
-    const int G = kv->persistent_wgs, S = 2 * (1 + 5 * kv->m->c.n_layers);
+    const int G = kv->persistent_wgs > 0 ? (kv->dataflow ? std::min(kv->cus, 256) : kv->persistent_wgs) : 0, S = 2 * (1 + 5 * kv->m->c.n_layers);
     if (G <= 0 || S > 512) return fail(SSD_ENOSUP, "no persistent kernel trace for this cache");
     if (cap < G * 512) return fail(SSD_ENOMEM, "cap %d < %d samples", cap, G * 512);
     HIP_TRY(hipMemcpy(out, kv->trace, sizeof(unsigned long long) * 512 * G, hipMemcpyDeviceToHost));
