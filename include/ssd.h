@@ -160,7 +160,7 @@ int ssd_warp_probs(const float* dev_logits, int rows, int V, const ssd_sample_co
  * ceil((len+R)/block_tokens) blocks, popping the free stack; a commit or rollback to new_len pushes back the
  * blocks with table index >= ceil(new_len/block_tokens), highest index first.  `free_stack` is returned bottom
  * first (the last entry is popped next).  dev_error_flag: bit 0 = the device allocator ran out of blocks, bit 1 = a
- * grid barrier of the persistent kernel timed out (the cache is unusable afterwards).  Any output pointer may be NULL. */
+ * wait inside a persistent kernel timed out (the cache is unusable afterwards).  Any output pointer may be NULL. */
 int ssd_kv_state(ssd_kv* kv, int seq, void* stream, int32_t* len, int32_t* n_pending, int32_t pending[2],
                  int32_t* n_owned, int32_t* block_table, int block_table_cap);
 int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, int32_t* n_free, int32_t* dev_error_flag);
@@ -175,11 +175,19 @@ int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, in
 int ssd_profile_begin(int kind);
 int ssd_profile_end(double* total_ms, int* launches);
 
-/* Barrier trace of the persistent forward kernel: with enable != 0 every later forward on `kv` records, per
- * workgroup and grid barrier, the 100 MHz wall clock at arrival and at release.  When `out` is non-NULL the
- * samples of the last forward are copied out first (synchronises `stream`): rows of 512 entries per workgroup,
- * out[wg*512 + 2*b] = arrival and out[wg*512 + 2*b+1] = release of barrier b for b < *n_samples / 2 (the rest of a
- * row is reserved); *n_wgs workgroups; cap >= 512 * workgroups. */
+/* Which kernels ran the last decoder forward on `kv` (host bookkeeping, no synchronisation):
+ * 0 none yet, 1 one launch per operator (fp32 storage, more than 16 rows, head_dim other than 64),
+ * 2 one persistent kernel with grid barriers between phases, 3 one persistent kernel whose phases are ordered by
+ * tagged data words (the default for bf16 storage and at most 16 rows; the environment variable
+ * SSD_FORWARD=barrier, read at ssd_kv_create, selects 2 instead). */
+int ssd_kv_last_forward_path(const ssd_kv* kv);
+
+/* Phase trace of the persistent forward kernels: with enable != 0 every later forward on `kv` records, per
+ * workgroup, 100 MHz wall-clock samples.  When `out` is non-NULL the samples of the last forward are copied out
+ * first (synchronises `stream`): rows of 512 entries per workgroup, *n_wgs workgroups, cap >= 512 * workgroups.
+ * Barrier kernel: out[wg*512 + 2*b] = arrival and [.. + 2*b+1] = release of grid barrier b for b < *n_samples / 2.
+ * Barrier-free kernel: entry 0 = start; entries 2 + 10*layer + 2*k and + 1 = operands staged / outputs stored of phase
+ * k (0 QKV, 1 attention, 2 output projection, 3 MLP, 4 partial sum), 0 where the workgroup has no item. */
 int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
                        int* n_samples);
 

@@ -10,7 +10,7 @@ EXPORTED_SYMBOLS = [
     "ssd_model_workspace_bytes", "ssd_model_create", "ssd_model_destroy", "ssd_kv_pool_bytes",
     "ssd_kv_workspace_bytes", "ssd_kv_create", "ssd_kv_destroy", "ssd_prefill", "ssd_draft_step", "ssd_verify",
     "ssd_kv_rollback", "ssd_kv_follow", "ssd_verify_from_probs", "ssd_warp_probs", "ssd_kv_state",
-    "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_trace_barriers", "ssd_strerror", "ssd_last_error",
+    "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_kv_last_forward_path", "ssd_trace_barriers", "ssd_strerror", "ssd_last_error",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library():
         "ssd_kv_free_stack": (i32, [vp, vp, C.POINTER(C.c_int32), i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
         "ssd_profile_begin": (i32, [i32]),
         "ssd_profile_end": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_int)]),
+        "ssd_kv_last_forward_path": (i32, [vp]),
         "ssd_trace_barriers": (i32, [vp, i32, vp, C.POINTER(C.c_uint64), i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
         "ssd_strerror": (C.c_char_p, [i32]),
         "ssd_last_error": (C.c_char_p, []),
@@ -190,6 +191,10 @@ class KVCache:
                                 self.mbps))
         return dict(len=ln.value, n_pending=npend.value, pending=list(pend)[:max(npend.value, 0)],
                     n_owned=own.value, table=list(table)[:own.value])
+
+    def last_forward_path(self):
+        """1 one launch per operator, 2 persistent kernel with grid barriers, 3 barrier-free persistent kernel."""
+        return load_library().ssd_kv_last_forward_path(self.handle)
 
     def free_stack(self):
         lib = load_library()

@@ -308,6 +308,7 @@ struct ssd_kv {
   u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
+  int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
   // host
   int32_t* mirror_host;
   std::vector<int> len_ub, npend_ub;
@@ -624,10 +625,12 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   if (kv->persistent_wgs > 0 && M <= kv->p_rows) {
     if (kv->dataflow) {
       const int rc = forward_dataflow(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
-      if (rc >= 0) return rc;
+      if (rc >= 0) { kv->last_path = 3; return rc; }
     }
+    kv->last_path = 2;
     return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
   }
+  kv->last_path = 1;
 
   EmbedArgs e;
   e.kv = kv->v; e.rows = rows; e.pcap = pcap; e.n_seqs = B; e.tokens = dev_tokens; e.tok_stride = tok_stride;
@@ -940,6 +943,8 @@ extern "C" int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, 
 }
 
 // ------------------------------------------------------------------------------------------------ barrier trace
+extern "C" int ssd_kv_last_forward_path(const ssd_kv* kv) { return kv ? kv->last_path : 0; }
+
 extern "C" int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
                                   int* n_samples) {
   if (!kv) return fail(SSD_EINVAL, "null handle");

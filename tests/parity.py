@@ -151,4 +151,4 @@ def run_verify_parity(workload, steps, K, beta, atol_logits, atol_probs, tempera
     if verbose:
         print(f"{workload}: {steps} steps K={K} beta={beta}: max|dlogits|={worst_l:.3g} max|dprobs|={worst_p:.3g} "
               f"accepted={ns}")
-    return dict(dlogits=worst_l, dprobs=worst_p, accepted=ns)
+    return dict(dlogits=worst_l, dprobs=worst_p, accepted=ns, path=pair.kv.last_forward_path())

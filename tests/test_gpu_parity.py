@@ -115,3 +115,48 @@ def test_tiny_topk_temperature_and_greedy():
     from tests.parity import run_verify_parity
     run_verify_parity("tiny", steps=4, K=3, beta=0.0, atol_logits=1e-5, atol_probs=1e-5, temperature=0.7, top_k=25)
     run_verify_parity("tiny", steps=4, K=3, beta=0.0, atol_logits=1e-5, atol_probs=1e-5, greedy=True)
+
+
+# ---- the barrier-free persistent forward (bf16 shapes, <= 16 rows) ------------------------------------------------
+@pytest.mark.gpu
+@pytest.mark.parametrize("n_prefix,K", [(250, 4), (254, 12), (600, 4), (1290, 7)])
+def test_mini_bf16_long_prefix_parts_and_boundaries(n_prefix, K):
+    """Prefix lengths whose new positions cross a 64-key chunk or a 256-key part, several parts, and more parts than
+    one merge flight takes (1290 keys: 6 parts), against the oracle; the barrier-free kernel must be the one that ran."""
+    from tests.parity import run_verify_parity
+    r = run_verify_parity("mini", steps=3, K=K, beta=0.3, atol_logits=2e-2, atol_probs=2e-2, n_prefix=n_prefix)
+    assert r["dlogits"] < 2e-2
+    assert r["path"] == 3, "the barrier-free persistent kernel did not run"
+
+
+@pytest.mark.gpu
+def test_barrier_and_barrier_free_kernels_agree(monkeypatch):
+    """Same model, prefix and drafts through both persistent kernels: logits agree to rounding (they share the
+    arithmetic definitions but not every summation order), decisions given equal probabilities are covered above."""
+    import torch
+    import synth_inputs as si
+    import paper_2505_15380_amd as ssd
+    wl = si.workload("mini")
+    shape = si.model_shape(wl["target"])
+    w = si.make_weights(shape, wl["seeds"]["target"])
+    toks = si.make_prefix(shape, 0, 300, wl["seeds"]["prefix"])
+    K, V = 4, shape["vocab"]
+    outs = []
+    for mode, want in (("barrier", 2), ("", 3)):
+        if mode:
+            monkeypatch.setenv("SSD_FORWARD", mode)
+        else:
+            monkeypatch.delenv("SSD_FORWARD", raising=False)
+        cfg = ssd.sample_config(beta=0.0, seed=3)
+        sess = ssd.SSDSession(shape, w, None, None, 1, K, len(toks) + 64, cfg, cfg)
+        sess.prefill(0, torch.from_numpy(toks).cuda())
+        x = torch.arange(5, 5 + K, dtype=torch.int32, device="cuda").reshape(1, K)
+        pd = torch.full((1, K, V), 1.0 / V, dtype=torch.float32, device="cuda")
+        logits = torch.zeros((1, K + 1, V), dtype=torch.float32, device="cuda")
+        ssd.ssd_verify(sess.target, sess.kv, 1, x, pd, K, cfg, 0,
+                       out=dict(n_accepted=sess.n_acc, next_token=sess.next, probs=None, logits=logits))
+        torch.cuda.synchronize()
+        assert sess.kv.last_forward_path() == want
+        outs.append(logits.cpu().numpy())
+    assert np.isfinite(outs[0]).all() and np.isfinite(outs[1]).all()
+    assert np.abs(outs[0] - outs[1]).max() < 2e-3
