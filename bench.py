@@ -138,7 +138,7 @@ def main():
     gu_ms = k_ms / max(k_n, 1)
     gu_gbs = fwd_bytes / (gu_ms * 1e-3) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_forward_persistent_half_b_k4.txt")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_k_forward_dataflow_half_b_k4.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch"):
