@@ -82,10 +82,36 @@ struct WarpArgs {
   size_t probs_stride;
 };
 
+constexpr int SBLOCK = 1024;          // threads of the two sampler kernels (16 waves): short unrolled loops, small code
+constexpr int SPER = 16;              // elements per thread: vocab <= 16384
+
+// Reductions over the 16 waves of a sampler workgroup through 16 LDS entries; all threads get the result.
+__device__ __forceinline__ float sblock_max(float v, float* s16) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s16[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = s16[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) r = fmaxf(r, s16[i]);
+  return r;
+}
+__device__ __forceinline__ float sblock_sum(float v, float* s16) {      // fixed order: waves ascending
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s16[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = s16[0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) r += s16[i];
+  return r;
+}
+
 // One workgroup per row.  Top-k keeps exactly k entries: everything above the k-th largest value, and of the
 // entries equal to it the ones with the lowest indices.
-__global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
-  __shared__ float s4[4];
+__global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) {
+  __shared__ float s16[16];
+  __shared__ int i16[16];
   __shared__ int hist[256];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_krem, sh_idxmax;
@@ -93,19 +119,32 @@ __global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
   const float* x = w.logits + (size_t)blockIdx.x * w.ld;
   float* p = w.probs + (size_t)blockIdx.x * w.probs_stride;
   const int V = w.V;
+  // the row is read once into registers (all loads in flight together)
+  float xv[SPER];
+#pragma unroll
+  for (int e = 0; e < SPER; ++e) {
+    const int i = tid + e * SBLOCK;
+    xv[e] = i < V ? x[i] : -INFINITY;
+  }
 
   if (w.greedy) {                                            // one-hot at the arg-max, lowest index on ties
     float best = -INFINITY; int bi = 0x7fffffff;
-    for (int i = tid; i < V; i += BLOCK) { const float v = x[i]; if (v > best) { best = v; bi = i; } }
-    const float mx = block_max(best, s4);
+#pragma unroll
+    for (int e = 0; e < SPER; ++e) { if (xv[e] > best) { best = xv[e]; bi = tid + e * SBLOCK; } }
+    const float mx = sblock_max(best, s16);
     int cand = (best == mx) ? bi : 0x7fffffff;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, WAVE));
-    __shared__ int c4[4];
-    if ((tid & 63) == 0) c4[tid >> 6] = cand;
+    if ((tid & 63) == 0) i16[tid >> 6] = cand;
     __syncthreads();
-    const int arg = min(min(c4[0], c4[1]), min(c4[2], c4[3]));
-    for (int i = tid; i < V; i += BLOCK) p[i] = (i == arg) ? 1.0f : 0.0f;
+    int arg = i16[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) arg = min(arg, i16[i]);
+#pragma unroll
+    for (int e = 0; e < SPER; ++e) {
+      const int i = tid + e * SBLOCK;
+      if (i < V) p[i] = (i == arg) ? 1.0f : 0.0f;
+    }
     return;
   }
 
@@ -117,13 +156,16 @@ __global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
     if (tid == 0) { sh_prefix = 0; sh_krem = w.top_k; }
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      hist[tid] = 0;
+      if (tid < 256) hist[tid] = 0;
       __syncthreads();
       const uint32_t prefix = sh_prefix;
       const uint32_t himask = pass ? (0xFFFFFFFFu << (shift + 8)) : 0u;
-      for (int i = tid; i < V; i += BLOCK) {
-        const uint32_t k = order_key(x[i]);
-        if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+#pragma unroll
+      for (int e = 0; e < SPER; ++e) {
+        if (tid + e * SBLOCK < V) {
+          const uint32_t k = order_key(xv[e]);
+          if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+        }
       }
       __syncthreads();
       if (tid == 0) {
@@ -140,12 +182,14 @@ __global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
     kth = sh_prefix;
     const int need_eq = sh_krem;                             // entries equal to kth that survive (>= 1)
     int eq = 0;
-    for (int i = tid; i < V; i += BLOCK) eq += (order_key(x[i]) == kth);
+#pragma unroll
+    for (int e = 0; e < SPER; ++e) eq += (tid + e * SBLOCK < V && order_key(xv[e]) == kth);
     eq = wave_sum_i(eq);
-    __shared__ int e4[4];
-    if ((tid & 63) == 0) e4[tid >> 6] = eq;
+    if ((tid & 63) == 0) i16[tid >> 6] = eq;
     __syncthreads();
-    const int n_eq = e4[0] + e4[1] + e4[2] + e4[3];
+    int n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) n_eq += i16[i];
     if (n_eq > need_eq) {                                    // a tie straddles the cut: rare, resolved serially
       if (tid == 0) {
         int seen = 0, im = V - 1;
@@ -157,35 +201,31 @@ __global__ void __launch_bounds__(BLOCK) k_warp_softmax(WarpArgs w) {
       idxmax = sh_idxmax;
     }
   }
-  // the row is read once into registers (all loads in flight together), then max / exp / sum / normalise
-  constexpr int PER = 64;                                   // V <= 16384
   const float T = w.temperature;
-  float z[PER];
+  float z[SPER];
   float mx = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int i = tid + e * BLOCK;
+  for (int e = 0; e < SPER; ++e) {
+    const int i = tid + e * SBLOCK;
     z[e] = -INFINITY;
     if (i < V) {
-      const float v = x[i];
-      const uint32_t k = order_key(v);
+      const uint32_t k = order_key(xv[e]);
       const bool keep = !use_k || k > kth || (k == kth && i <= idxmax);
-      if (keep) z[e] = v / T;
+      if (keep) z[e] = xv[e] / T;
     }
+    mx = fmaxf(mx, z[e]);
   }
-#pragma unroll
-  for (int e = 0; e < PER; ++e) mx = fmaxf(mx, z[e]);
-  mx = block_max(mx, s4);
+  mx = sblock_max(mx, s16);
   float sum = 0.f;
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
+  for (int e = 0; e < SPER; ++e) {
     z[e] = (z[e] == -INFINITY) ? 0.f : expf(z[e] - mx);
     sum += z[e];
   }
-  sum = block_sum(sum, s4);
+  sum = sblock_sum(sum, s16);
 #pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int i = tid + e * BLOCK;
+  for (int e = 0; e < SPER; ++e) {
+    const int i = tid + e * SBLOCK;
     if (i < V) p[i] = z[e] / sum;
   }
 }
@@ -210,9 +250,39 @@ struct AcceptArgs {
   int seq0;
 };
 
-// Fixed-point weight of the canonical sampler: floor(w * 2^40) for w in [0, 1].
+// Fixed-point weight of the canonical sampler: floor(w * 2^40) for a non-negative float w < 2^23, exactly (the
+// product is a shift of the 24-bit significand; subnormals are below 2^-40 and give 0).
 __device__ __forceinline__ unsigned long long fix40(float w) {
-  return (unsigned long long)((double)w * 1099511627776.0);
+  const uint32_t u = __float_as_uint(w);
+  const int ex = (int)((u >> 23) & 255u);
+  if (ex == 0 || (u >> 31)) return 0ull;
+  const unsigned long long mant = (unsigned long long)((u & 0x7FFFFFu) | 0x800000u);
+  const int sh = ex - 127 + 17;                              // value = mant * 2^(ex - 150); times 2^40
+  return sh >= 0 ? (mant << sh) : (sh > -24 ? (mant >> (-sh)) : 0ull);
+}
+
+// Exclusive prefix sum of one 64-bit value per thread over the 1024 threads of a sampler workgroup (integer: exact
+// in any order).  w16: 16 entries of LDS.
+__device__ __forceinline__ unsigned long long sblock_excl_scan_u64(unsigned long long v, unsigned long long* w16,
+                                                                   unsigned long long* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned long long inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long t = __shfl_up(inc, o, WAVE);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) w16[wave] = inc;
+  __syncthreads();
+  unsigned long long base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (i < wave) base += w16[i];
+    tot += w16[i];
+  }
+  *total = tot;
+  return base + inc - v;
 }
 
 // One workgroup per sequence.
@@ -223,9 +293,8 @@ __device__ __forceinline__ unsigned long long fix40(float w) {
 //     summation tree): smallest j whose inclusive prefix exceeds floor(total * u).
 //  3. the last workgroup to finish commits every sequence in ascending order: len += pending + n, pending =
 //     emitted token, blocks past the new length go back to the free stack.
-__global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
-  __shared__ unsigned long long part[BLOCK];
-  __shared__ unsigned long long w4[4];
+__global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) {
+  __shared__ unsigned long long w16[16];
   __shared__ int sh_n, sh_tok, sh_last;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int K = a.K, V = a.V;
@@ -252,31 +321,25 @@ __global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
   const float u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
   const float* prow = pt + (size_t)n * V;
   const float* drow = pd + (size_t)n * V;                   // only read when n < K
-  const int per = (V + BLOCK - 1) / BLOCK;                  // contiguous span of indices per thread (<= 64)
+  const int per = (V + SBLOCK - 1) / SBLOCK;                // contiguous span of indices per thread (<= SPER)
   const int j0 = tid * per;
-  constexpr int PER = 64;
   int fallback = 0;
   bool residual = n < K;
-  unsigned long long total;
-  float wgt[PER];
+  unsigned long long total, excl, mine;
+  float wgt[SPER];
   for (;;) {
     // the thread's span of weights, all loads in flight together
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
+    for (int e = 0; e < SPER; ++e) {
       const int j = j0 + e;
       wgt[e] = 0.f;
       if (e < per && j < V) wgt[e] = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
     }
-    unsigned long long s = 0;
+    mine = 0;
 #pragma unroll
-    for (int e = 0; e < PER; ++e) s += fix40(wgt[e]);
-    part[tid] = s;
-    const unsigned long long ws = wave_sum_u64(s);
-    __syncthreads();
-    if ((tid & 63) == 0) w4[tid >> 6] = ws;
-    __syncthreads();
-    total = w4[0] + w4[1] + w4[2] + w4[3];
-    if (total == 0 && residual) { residual = false; fallback = 1; __syncthreads(); continue; }
+    for (int e = 0; e < SPER; ++e) mine += fix40(wgt[e]);
+    excl = sblock_excl_scan_u64(mine, w16, &total);          // sum of the spans before this thread's, and of all
+    if (total == 0 && residual) { residual = false; fallback = 1; continue; }
     break;
   }
   if (total == 0) {
@@ -284,14 +347,12 @@ __global__ void __launch_bounds__(BLOCK) k_accept(AcceptArgs a) {
   } else {
     const unsigned long long Ru = (unsigned long long)(u * 16777216.0f);
     const unsigned long long tgt = (__umul64hi(total, Ru) << 40) | ((total * Ru) >> 24);   // floor(total*Ru / 2^24)
-    unsigned long long excl = 0;                             // sum of the spans before this thread's
-    for (int t = 0; t < tid; ++t) excl += part[t];
-    if (excl <= tgt && tgt < excl + part[tid]) {
+    if (excl <= tgt && tgt < excl + mine) {
       unsigned long long c = excl;
       int tok = min(j0 + per, V) - 1;
       bool found = false;
 #pragma unroll
-      for (int e = 0; e < PER; ++e) {
+      for (int e = 0; e < SPER; ++e) {
         c += fix40(wgt[e]);
         if (!found && c > tgt) { tok = j0 + e; found = true; }
       }

@@ -774,14 +774,14 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
     w.ld = R * V;                       // one row per sequence
     w.probs = probs_out ? probs_out : kv->probs;
     w.probs_stride = probs_out ? probs_seq_stride : (size_t)V;
-    hipLaunchKernelGGL(k_warp_softmax, dim3(B), dim3(BLOCK), 0, st, w);
+    hipLaunchKernelGGL(k_warp_softmax, dim3(B), dim3(SBLOCK), 0, st, w);
     a.pt = w.probs; a.pt_seq_stride = w.probs_stride;
   } else {
     w.logits = kv->logits + (size_t)(pcap - 1) * V;   // row of the last pending token, then the K drafts
     // rows pcap-1 .. R-1 of every sequence are consecutive only when pcap == 1 (a target cache)
     w.probs = probs_out ? probs_out : kv->probs;
     w.probs_stride = V;
-    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(BLOCK), 0, st, w);
+    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(SBLOCK), 0, st, w);
     a.pt = w.probs; a.pt_seq_stride = (size_t)(K + 1) * V;
   }
   LAUNCH_CHECK();
@@ -790,7 +790,7 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
   a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
   a.kv = kv->v; a.seq0 = 0;
   a.slot_base = slot_base;
-  hipLaunchKernelGGL(k_accept, dim3(B), dim3(BLOCK), 0, st, a);
+  hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, st, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -886,7 +886,7 @@ extern "C" int ssd_verify_from_probs(const float* dev_pt, const float* dev_pd, c
   a.pt = dev_pt; a.pt_seq_stride = (size_t)(K + 1) * V; a.pd = dev_pd; a.x = dev_tokens; a.uniforms = dev_uniforms;
   a.B = B; a.K = K; a.V = V; a.beta = beta; a.n_acc = dev_n_accepted; a.next_tok = dev_next_token; a.tok_stride = 1;
   a.flags = dev_flags;
-  hipLaunchKernelGGL(k_accept, dim3(B), dim3(BLOCK), 0, (hipStream_t)stream, a);
+  hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, (hipStream_t)stream, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -899,7 +899,7 @@ extern "C" int ssd_warp_probs(const float* dev_logits, int rows, int V, const ss
   WarpArgs w;
   w.logits = dev_logits; w.ld = V; w.V = V; w.temperature = cfg->temperature; w.top_k = cfg->top_k; w.greedy = cfg->greedy;
   w.probs = dev_probs; w.probs_stride = V;
-  hipLaunchKernelGGL(k_warp_softmax, dim3(rows), dim3(BLOCK), 0, (hipStream_t)stream, w);
+  hipLaunchKernelGGL(k_warp_softmax, dim3(rows), dim3(SBLOCK), 0, (hipStream_t)stream, w);
   LAUNCH_CHECK();
   return SSD_OK;
 }
