@@ -50,6 +50,16 @@ constexpr int DF_ATT_UNIT = 4096 + 512 + 512 + 4096 + 4096 + 128;      // Q | ne
 constexpr int DF_LDS_WORDS = (DF_AW + DF_SQ_WORDS + DF_RED_WORDS) > 2 * DF_ATT_UNIT ? (DF_AW + DF_SQ_WORDS + DF_RED_WORDS)
                                                                                   : 2 * DF_ATT_UNIT;
 
+#ifndef DF_HINT_OWN
+#define DF_HINT_OWN 9      // bit k set: phase kind k (0 QKV, 1 attention, 2 O, 3 MLP, 4 sum) watches a word of its OWN operands
+#endif
+#ifndef DF_HINT_SLEEP
+#define DF_HINT_SLEEP 2
+#endif
+#ifndef DF_HINT_LAST
+#define DF_HINT_LAST 1
+#endif
+
 struct DArgs {
   int n_layers, d, nq, nkv, ffn, vocab, n_embed;
   float eps, scale;
@@ -102,7 +112,7 @@ __device__ __forceinline__ void df_wait_hint(const u64* word, uint32_t tag, uint
   for (int i = 0; i < (1 << 14); ++i) {
     if ((uint32_t)(ld_word(word) >> 32) == tag) return;
     if ((i & 63) == 63 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0) return;
-    __builtin_amdgcn_s_sleep(16);
+    __builtin_amdgcn_s_sleep(DF_HINT_SLEEP);
   }
 }
 
@@ -617,7 +627,10 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 #pragma unroll
         for (int i = 0; i < DF_RW; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag2);
         if (all) break;
-        if (spins == 0) df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, a.tag, err);
+        if (spins == 0) {
+          if (DF_HINT_OWN & 16) df_wait_hint(part2, tag2, err);
+          else df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, a.tag, err);
+        }
         if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
           __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
           bad = true;
@@ -857,7 +870,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
       }
     }
-    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64, a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
+    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64, (DF_HINT_OWN & 2) ? q + (size_t)(it.b * R) * nqd + (it.kvh * G) * 64 : a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
 #pragma unroll
     for (int u = 0; u < DF_B; ++u) {
       const int idx = u * 256 + ut;
@@ -1066,7 +1079,12 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
     x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = s_qkv;
     x.bias = Y.bqkv; x.out = a.q + (size_t)l * a.st_q; x.kvn = a.kvn + (size_t)l * a.st_kvn;
-    if (l > 0) { x.hint = a.part2 + (size_t)((l - 1) & 1) * a.st_part2; x.hint_tag = df_tag2(a, l - 1); }
+#if DF_HINT_LAST
+    if (DF_HINT_OWN & 1) { x.hint = x.A + (size_t)(a.rows.M - 1) * a.d + (a.d - 32); x.hint_tag = a.tag; }   // a word of the last sum task
+#else
+    if (DF_HINT_OWN & 1) { x.hint = x.A; x.hint_tag = a.tag; }
+#endif
+    else if (l > 0) { x.hint = a.part2 + (size_t)((l - 1) & 1) * a.st_part2; x.hint_tag = df_tag2(a, l - 1); }
     return x;
   };
   auto make_o = [&](int l) {
@@ -1079,7 +1097,8 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     x.h_in = a.h + hi * a.st_h; x.h_out = a.h + (hi + 1) * a.st_h; x.hg_out = a.hg + (hi + 1) * a.st_h;
     x.sq_out = a.sq + (hi + 1) * a.st_sq;
     x.gain_next = Y.ln2;
-    x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = a.tag;
+    if (DF_HINT_OWN & 4) { x.hint = x.A; x.hint_tag = a.tag; }
+    else { x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = a.tag; }
     return x;
   };
   auto make_swiglu = [&](int l) {
@@ -1087,7 +1106,8 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
     x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0;
-    x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag;
+    if (DF_HINT_OWN & 8) { x.hint = a.hg + (size_t)(2 * l + 1) * a.st_h; x.hint_tag = a.tag; }
+    else { x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag; }
     return x;
   };
   auto make_head = [&]() {
