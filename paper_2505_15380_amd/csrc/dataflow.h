@@ -89,6 +89,7 @@ struct DArgs {
   size_t st_h, st_sq, st_q, st_kvn, st_att_p;   // strides in words
   int NP, n_parts;
   int g_mlp;              // workgroups [0, g_mlp) take the MLP items; the phases with few items start on the workgroups after them
+  int small_stride;       // 2: a small-phase item has a workgroup to itself; 1: two items per workgroup
   uint32_t* bar;          // [0] arrivals, [32] flag, [64] error flag
   unsigned long long* trace;
 };
@@ -181,7 +182,7 @@ struct DPhase {
   const void* W0;
   const void* W1;
   int N, K, gs, items;    // gs: k-splits, always 1 here (the field the shared k-range helper reads)
-  int shift;              // item i of round 0 runs on unit (i + shift) % units
+  int shift, stride;      // item i of round 0 runs on unit (shift + stride * i) % units
   const u64* hint;        // a word of the preceding phase's operands (see df_wait_hint), or null
   uint32_t hint_tag;
   int layer;
@@ -275,9 +276,13 @@ __device__ __forceinline__ void frag_from_lds(const uint32_t* p, u32x4& hi, u32x
 #endif
 #define DF_STAMP(slot) do { if (a.trace && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * 512 + (slot)] = wall_clock64(); } while (0)
 
-__device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU) {
+// Item of round 0 that `unit` takes when items start at unit `shift` and take every `stride`-th unit (stride 2: one
+// item per workgroup, its other unit idles, so the item's waves have their SIMDs to themselves); a huge number where none.
+__device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU, int stride = 1) {
   int i = unit - shift;
-  return i < 0 ? i + NU : i;
+  if (i < 0) i += NU;
+  if (stride == 2) return (i & 1) ? 0x3FFFFFFF : (i >> 1);
+  return i;
 }
 
 // One GEMM phase (QKV, output projection, head); the caller skips it for a workgroup none of whose units has an
@@ -292,7 +297,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int usel = wave >> 2, uw = wave & 3, ut = tid & 255;
   const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
-  const int uitem = df_item_of_unit(unit, ph.shift, NU);
+  const int uitem = df_item_of_unit(unit, ph.shift, NU, ph.stride);
   uint32_t* As = lds;
   float* sqs = (float*)(lds + DF_AW);
   float (*red)[2][256] = (float (*)[2][256])((float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048);
@@ -1072,12 +1077,14 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int n_qkv = (a.nq + 2 * a.nkv) * 2, ntile = (a.rows.R * (a.nq / a.nkv) + 15) >> 4,
             n_att = a.n_seqs * a.nkv * a.n_parts * ntile, n_o = np, n_gu = a.ffn >> 4,
             n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
-  const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + n_qkv) % NU, s_o = (s_att + n_att) % NU;
+  const int st = a.small_stride;
+  const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + st * n_qkv) % NU, s_o = (s_att + st * n_att) % NU,
+            s_red = (s_o + st * n_o) % NU;
   auto make_qkv = [&](int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
-    x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = s_qkv;
+    x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = s_qkv; x.stride = st;
     x.bias = Y.bqkv; x.out = a.q + (size_t)l * a.st_q; x.kvn = a.kvn + (size_t)l * a.st_kvn;
 #if DF_HINT_LAST
     if (DF_HINT_OWN & 1) { x.hint = x.A + (size_t)(a.rows.M - 1) * a.d + (a.d - 32); x.hint_tag = a.tag; }   // a word of the last sum task
@@ -1092,7 +1099,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     DPhase x = DPhase{};
     x.layer = l;
     x.A = a.attn + (size_t)l * a.st_q;
-    x.W0 = Y.wo; x.W1 = Y.wo; x.N = a.d; x.K = nqd; x.gs = 1; x.items = n_o; x.shift = s_o;
+    x.W0 = Y.wo; x.W1 = Y.wo; x.N = a.d; x.K = nqd; x.gs = 1; x.items = n_o; x.shift = s_o; x.stride = st;
     const size_t hi = (size_t)(2 * l);
     x.h_in = a.h + hi * a.st_h; x.h_out = a.h + (hi + 1) * a.st_h; x.hg_out = a.hg + (hi + 1) * a.st_h;
     x.sq_out = a.sq + (hi + 1) * a.st_sq;
@@ -1105,7 +1112,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
-    x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0;
+    x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0; x.stride = 1;
     if (DF_HINT_OWN & 8) { x.hint = a.hg + (size_t)(2 * l + 1) * a.st_h; x.hint_tag = a.tag; }
     else { x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag; }
     return x;
@@ -1113,22 +1120,23 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   auto make_head = [&]() {
     DPhase x = DPhase{};
     x.A = a.hg + (size_t)(2 * L) * a.st_h; x.sq = a.sq + (size_t)(2 * L) * a.st_sq;
-    x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.logits = a.logits;
+    x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.stride = 1; x.logits = a.logits;
     return x;
   };
   // which phase kinds this wave's unit / this workgroup has a round-0 item in
   const int wave_k = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int unit = blockIdx.x * 2 + (wave_k >> 2);
-  auto has = [&](int u, int shift, int items) { return df_item_of_unit(u, shift, NU) < items; };
-  const int n_red = a.rows.M * np, s_red = s_qkv;
+  auto has = [&](int u, int shift, int items, int stride = 1) { return df_item_of_unit(u, shift, NU, stride) < items; };
+  const int n_red = a.rows.M * np;
   const int u0 = blockIdx.x * 2, u1 = u0 + 1;
-  const bool g_q = has(u0, s_qkv, n_qkv) || has(u1, s_qkv, n_qkv) || n_qkv > NU, g_a = has(u0, s_att, n_att) || has(u1, s_att, n_att),
-             g_o = has(u0, s_o, n_o) || has(u1, s_o, n_o), g_g = (int)blockIdx.x < a.g_mlp,
+  const bool g_q = has(u0, s_qkv, n_qkv, st) || has(u1, s_qkv, n_qkv, st) || st * n_qkv > NU,
+             g_a = has(u0, s_att, n_att, st) || has(u1, s_att, n_att, st),
+             g_o = has(u0, s_o, n_o, st) || has(u1, s_o, n_o, st), g_g = (int)blockIdx.x < a.g_mlp,
              g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
 
   df_embed_phase(a);
   if (df_start_barrier(a, &sdead)) return;
-  const DAttItem ait = df_att_item(a, df_item_of_unit(unit, s_att, NU), ntile, wave_k & 3, threadIdx.x & 63);
+  const DAttItem ait = df_att_item(a, df_item_of_unit(unit, s_att, NU, st), ntile, wave_k & 3, threadIdx.x & 63);
   if (threadIdx.x < a.rows.M) {                           // per-row constants of the launch: position, active, block of the new key
     const int m = threadIdx.x;
     const int pos = ld_state(a.rows.pos + m);
