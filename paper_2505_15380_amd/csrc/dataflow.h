@@ -104,6 +104,28 @@ __device__ __forceinline__ uint32_t split_payload(float x) {
   return (h >> 16) | ((uint32_t)f_to_bf16(x - __uint_as_float(h)) << 16);
 }
 
+// All-reduce over the 16 lanes of a DPP row (lanes 16k .. 16k+15) with data-parallel primitives instead of LDS
+// shuffles: pairs, quads (quad_perm), half rows (row_half_mirror), rows (row_mirror).  Every step combines a lane's
+// value with the value of a lane of the complementary group, so all 16 lanes end with bit-identical results.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<0xB1>(v);       // quad_perm [1,0,3,2]
+  v += dpp_f<0x4E>(v);       // quad_perm [2,3,0,1]
+  v += dpp_f<0x141>(v);      // row_half_mirror
+  v += dpp_f<0x140>(v);      // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  v = fmaxf(v, dpp_f<0x141>(v));
+  v = fmaxf(v, dpp_f<0x140>(v));
+  return v;
+}
+
 // A workgroup that arrives at a phase long before its operands would poll them the whole time, and the polls of all
 // such workgroups load the fabric that the producers' stores travel through.  After a first failed flight a wave
 // therefore watches one word of the operands of the PRECEDING phase (one hand-over earlier) with a single
@@ -387,8 +409,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
     float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
     if (ph.sq) {
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+      sq = row16_sum(sq);
       const float inv = 1.0f / sqrtf(sq / (float)ph.K + a.eps);
       v0 *= inv;
       v1 *= inv;
@@ -438,8 +459,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
           st_word(ph.hg_out + (size_t)row * ph.N + n1, split_payload(v1 * gn1), a.tag);
           q2 = v0 * v0 + v1 * v1;
         }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) q2 += __shfl_xor(q2, o, WAVE);
+        q2 = row16_sum(q2);
         if (col == 0 && row < M) st_wordf(ph.sq_out + (size_t)row * (ph.N >> 5) + pair, q2, a.tag);
       }
     }
@@ -549,8 +569,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     __syncthreads();
     float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
     float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
+    sq = row16_sum(sq);
     const float inv = 1.0f / sqrtf(sq / (float)ph.K + a.eps);
     v0 *= inv;
     v1 *= inv;
@@ -632,7 +651,8 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 #pragma unroll
         for (int i = 0; i < DF_RW; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag2);
         if (all) break;
-        if (spins == 0) {
+        // a workgroup that comes here from its own MLP item is not early: no hint for it
+        if (spins == 0 && (int)blockIdx.x >= a.g_mlp) {
           if (DF_HINT_OWN & 16) df_wait_hint(part2, tag2, err);
           else df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, a.tag, err);
         }
@@ -857,6 +877,12 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
   u64* att_p = a.att_p + (size_t)layer * a.st_att_p;
   const int* rowpos = srow + it.b * R;                 // positions of the sequence's rows
   const float sc2 = a.scale * 1.44269504088896340736f;
+  int qpos[4];                                         // positions of the 4 query rows this lane holds scores of
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int qr = r0 + 4 * g + r;
+    qpos[r] = qr < RG ? rowpos[qr / G] : -1;
+  }
   bool bad = false;
   // ---- one flight per thread: the queries of the tile's rows and this launch's keys / values of the kv head
   if (it.valid) {
@@ -937,11 +963,14 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
       z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[1]), k1, z, 0, 0, 0);
       s[t] = z;
     }
+#ifdef SSD_TRACE_FINE
+    if (s[0][0] == 123456.f && s[3][3] == 1.f) *sdead = 2;
+    DF_AFINE(6);
+#endif
     // element (reg r, tile t) = (query row r0 + 4g + r, key kbase + 16t + c16)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int qr = r0 + 4 * g + r;
-      const int pos = qr < RG ? rowpos[qr / G] : -1;
+      const int pos = qpos[r];
       float mx = -INFINITY;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -949,8 +978,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         s[t][r] = ok ? s[t][r] * sc2 : -INFINITY;
         mx = fmaxf(mx, s[t][r]);
       }
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+      mx = row16_max(mx);
       float sum = 0.f;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -958,12 +986,15 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         Pw[(4 * g + r) * 64 + 16 * t + c16] = p;
         sum += p;
       }
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, WAVE);
+      sum = row16_sum(sum);
       mrow[r] = mx;
       lrow[r] = sum;
     }
     __builtin_amdgcn_wave_barrier();
+#ifdef SSD_TRACE_FINE
+    if (lrow[0] == 123456.f && lrow[3] == 1.f) *sdead = 2;
+    DF_AFINE(7);
+#endif
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const u32x4* pp = (const u32x4*)(Pw + c16 * 64 + ks * 32 + g * 8);
