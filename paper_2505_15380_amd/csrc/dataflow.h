@@ -377,13 +377,17 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
     const uint32_t* arow_p = As + arow * (ph.K + 4) + g * 8;
     if (valid) {
+      // all operand fragments first (their LDS latencies overlap), then the products
+      u32x4 fh[PF_K], fl[PF_K];
+#pragma unroll
+      for (int u = 0; u < PF_K; ++u) {
+        fh[u] = u32x4{0u, 0u, 0u, 0u};
+        fl[u] = fh[u];
+        if (kb + u < ke && arow < M) frag_from_lds(arow_p + (kb + u) * 32, fh[u], fl[u]);
+      }
 #pragma unroll
       for (int u = 0; u < PF_K; ++u)
-        if (kb + u < ke) {
-          u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
-          if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
-          mfma_pair(xh, xl, wl.b0[u], wl.b1[u], acc0, acc1);
-        }
+        if (kb + u < ke) mfma_pair(fh[u], fl[u], wl.b0[u], wl.b1[u], acc0, acc1);
       for (int kt = kb + PF_K; kt < ke; ++kt) {                       // waves with more than PF_K k-tiles
         u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
         if (arow < M) frag_from_lds(arow_p + kt * 32, xh, xl);
@@ -543,13 +547,17 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     if (valid) {
       const u32x4* w0 = (const u32x4*)ph.W0 + (size_t)item * KT * 64 + lane;
       const u32x4* w1 = (const u32x4*)ph.W1 + (size_t)item * KT * 64 + lane;
+      // all operand fragments first (their LDS latencies overlap), then the products
+      u32x4 fh[PF_K], fl[PF_K];
+#pragma unroll
+      for (int u = 0; u < PF_K; ++u) {
+        fh[u] = u32x4{0u, 0u, 0u, 0u};
+        fl[u] = fh[u];
+        if (kb + u < ke && arow < M) frag_from_lds(arow_p + (kb + u) * 32, fh[u], fl[u]);
+      }
 #pragma unroll
       for (int u = 0; u < PF_K; ++u)
-        if (kb + u < ke) {
-          u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
-          if (arow < M) frag_from_lds(arow_p + (kb + u) * 32, xh, xl);
-          mfma_pair(xh, xl, pre.b0[u], pre.b1[u], acc0, acc1);
-        }
+        if (kb + u < ke) mfma_pair(fh[u], fl[u], pre.b0[u], pre.b1[u], acc0, acc1);
       for (int kt = kb + PF_K; kt < ke; ++kt) {
         u32x4 xh = u32x4{0u, 0u, 0u, 0u}, xl = xh;
         if (arow < M) frag_from_lds(arow_p + kt * 32, xh, xl);
