@@ -40,7 +40,7 @@ namespace ssd {
 typedef unsigned long long u64;
 constexpr int DF_B = 12;                  // tagged words a thread keeps in flight while it stages operands
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
-constexpr int DF_ATT_ROWS = 64;           // query rows of one attention item: rows of a sequence x heads of a group
+constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
 constexpr int DF_NPF = 4;                 // attention parts merged per flight
 constexpr long DF_SPIN_LIMIT = 1L << 18;
 // LDS words: staging | sums of squares | unit reduction buffers, overlaid by the attention buffers of the two units
