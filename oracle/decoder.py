@@ -17,19 +17,30 @@ class Model:
         self.w = {k: (None if v is None else np.asarray(v, dtype=np.float64)) for k, v in weights.items()}
 
 
+def round_to_bf16_storage(x):
+    """Values as a bf16 cache would hold them: rounded to nearest even on the upper 16 bits of their fp32 form."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
 class Cache:
     """Contiguous per-layer key/value store: k[l], v[l] are [capacity, n_kv_heads, head_dim] fp64;
-    positions 0..length-1 are valid."""
+    positions 0..length-1 are valid.  The definition keeps keys and values exact (store=None).  store="bf16"
+    models the storage format of the bf16 configurations instead: every key/value is rounded to bf16 when it is
+    written, everything else stays fp64.  Tests use it to separate what the cache format costs (a property of the
+    configuration) from what the arithmetic of an implementation costs."""
 
-    def __init__(self, shape, capacity):
+    def __init__(self, shape, capacity, store=None):
         nl, nkv, hd = shape["n_layers"], shape["n_kv_heads"], shape["head_dim"]
         self.k = np.zeros((nl, capacity, nkv, hd))
         self.v = np.zeros((nl, capacity, nkv, hd))
         self.length = 0
+        self.store = store
 
     def copy(self):
         c = Cache.__new__(Cache)
-        c.k, c.v, c.length = self.k.copy(), self.v.copy(), self.length
+        c.k, c.v, c.length, c.store = self.k.copy(), self.v.copy(), self.length, self.store
         return c
 
 
@@ -85,6 +96,8 @@ def forward_rows(model, cache, tokens, with_head=True):
         v = qkv[:, (nq + nkv) * hd:].reshape(R, nkv, hd)
         q = rope(q, pos, sh["rope_base"])
         k = rope(k, pos, sh["rope_base"])
+        if getattr(cache, "store", None) == "bf16":
+            k, v = round_to_bf16_storage(k), round_to_bf16_storage(v)
         cache.k[l, L:L + R] = k
         cache.v[l, L:L + R] = v
         att = np.empty((R, nq, hd))

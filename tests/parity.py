@@ -21,7 +21,7 @@ class Pair:
     """One model on both sides with one sequence slot set."""
 
     def __init__(self, shape_name, seed, max_positions, max_seqs=1, max_rows=16, n_blocks=None, block_tokens=16,
-                 pending_cap=1, weights=None, shape=None):
+                 pending_cap=1, weights=None, shape=None, store=None):
         self.shape = shape or si.model_shape(shape_name)
         self.w = weights if weights is not None else si.make_weights(self.shape, seed)
         self.omodel = OD.Model(self.shape, self.w)
@@ -31,7 +31,7 @@ class Pair:
             n_blocks = max_seqs * mbps
         self.kv = ssd.KVCache(self.gmodel, max_seqs, max_rows, n_blocks, block_tokens, mbps, pending_cap)
         self.alloc = PagedAllocator(n_blocks, block_tokens, max_seqs, mbps)
-        self.ocache = [OD.Cache(self.shape, max_positions) for _ in range(max_seqs)]
+        self.ocache = [OD.Cache(self.shape, max_positions, store=store) for _ in range(max_seqs)]   # store: see oracle.decoder.Cache
         self.pending = [None] * max_seqs
         self.max_rows = max_rows
 
@@ -125,7 +125,7 @@ def verify_parity_step(pair, cfg_dict, K, step, rng, atol_logits, atol_probs, se
 
 
 def run_verify_parity(workload, steps, K, beta, atol_logits, atol_probs, temperature=1.0, top_k=0, greedy=False,
-                      n_prefix=None, verbose=False, atol_kv=None):
+                      n_prefix=None, verbose=False, atol_kv=None, store=None):
     wl = si.workload(workload)
     shape = si.model_shape(wl["target"])
     n_text, n_speech = wl["prefix"]
@@ -133,7 +133,7 @@ def run_verify_parity(workload, steps, K, beta, atol_logits, atol_probs, tempera
         n_text, n_speech = 0, n_prefix
     toks = si.make_prefix(shape, n_text, n_speech, wl["seeds"]["prefix"])
     max_pos = len(toks) + steps * (K + 1) + 32
-    pair = Pair(wl["target"], wl["seeds"]["target"], max_pos, max_rows=16)
+    pair = Pair(wl["target"], wl["seeds"]["target"], max_pos, max_rows=16, store=store)
     pair.prefill(0, toks)
     atol_kv = atol_kv if atol_kv is not None else atol_logits
     pair.check_state(0, atol_kv)

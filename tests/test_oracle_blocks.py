@@ -154,3 +154,27 @@ def test_warp_ties_and_greedy():
     assert g[0].tolist() == [0, 1, 0, 0, 0, 0]
     # top_k >= V and top_k = 0 both mean "no truncation"
     np.testing.assert_allclose(warp_probs(z, 1.0, top_k=6), warp_probs(z, 1.0, top_k=0))
+
+
+def test_bf16_storage_option_only_rounds_keys_and_values():
+    """store="bf16" rounds what is written to the cache (round to nearest even on the upper 16 bits) and nothing
+    else: the rounding function agrees with torch's bfloat16 cast, cached values are exactly representable,
+    the first row's logits are unchanged (its own key/value rounding aside, checked against the exact cache within
+    the size of that rounding), and the exact cache is untouched by default."""
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    from oracle import decoder as OD
+    x = np.random.default_rng(0).standard_normal(4096) * np.array([1e-3, 1.0, 50.0, 1e4]).repeat(1024)
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(OD.round_to_bf16_storage(x), want)
+    shape = si.model_shape("tiny")
+    m = OD.Model(shape, si.make_weights(shape, 3))
+    toks = si.make_prefix(shape, 0, 24, 1)
+    ce, cb = OD.Cache(shape, 32), OD.Cache(shape, 32, store="bf16")
+    le, lb = OD.forward_rows(m, ce, toks), OD.forward_rows(m, cb, toks)
+    assert ce.store is None
+    assert np.array_equal(cb.k, OD.round_to_bf16_storage(cb.k)) and np.array_equal(cb.v, OD.round_to_bf16_storage(cb.v))
+    assert not np.array_equal(ce.k, cb.k)
+    d = np.abs(le - lb).max()
+    assert 0 < d < 5e-3                          # bf16 keys/values perturb the logits a little, and only a little
