@@ -127,4 +127,201 @@ __global__ void __launch_bounds__(WAVE) k_attn_combine(AttnArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------ matrix-core variant
+// The same operation for bf16 caches with 16-token blocks and head_dim 64 or 128, for launches with many rows
+// (batched verification).  Work item = (part of 256 key positions, kv head, sequence); wave w of the workgroup
+// takes keys [256 part + 64 w, +64) and reads them ONCE, as MFMA operand fragments straight from the cache: a
+// K fragment is 8 consecutive dims of one cached key row, a V fragment 8 consecutive tokens of one dim of the
+// token-minor value layout.  The query rows that share the keys - R rows of the sequence x the G query heads of
+// the group - are walked in tiles of 16: S = Q K^T (queries as hi + lo bf16, so they are not rounded), a masked
+// softmax per row over the wave's 64 keys in the base-2 domain, O = P V with P split the same way.  The four
+// waves' partials are merged in ascending key order through LDS and stored as one partial per (row, head, part);
+// k_attn_combine_parts merges the parts in ascending order.  Parts are cut at absolute positions, so a row's
+// bits do not depend on which other rows share the launch.
+constexpr int ATT_PART_KEYS = 256;
+
+template <int HD>
+__global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
+  constexpr int KS = HD / 32, DT = HD / 16;
+  __shared__ __attribute__((aligned(16))) float Pw[4][16 * 64];
+  __shared__ __attribute__((aligned(16))) float MO[4][16 * HD];
+  __shared__ float ML[4][16][2];
+  const int part = blockIdx.x, kvh = blockIdx.y, brel = blockIdx.z;
+  const int seq = a.rows.seq0 + brel;
+  const int R = a.rows.R, nkv = a.kv.nkv, G = a.nq / nkv, RG = R * G;
+  const int m_first = brel * R;
+  const int pos_max = a.rows.pos[m_first + R - 1];
+  const int pbase = part * ATT_PART_KEYS;
+  if (pbase > pos_max) return;                           // no row of this sequence reaches the part
+  const int tid = threadIdx.x, lane = tid & 63, uw = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c16 = lane & 15;
+  const int kbase = pbase + 64 * uw;
+  const bool wlive = kbase <= pos_max;                   // wave-uniform
+
+  // fragments of the wave's 64 keys and values (masked keys may read any valid block)
+  u32x4 kf[4][KS], vf[2][DT];
+  if (wlive) {
+    const size_t plane = (size_t)a.kv.n_blocks * nkv * 16 * HD;
+    const bf16_t* kp = (const bf16_t*)a.kv.pool + (size_t)(2 * a.layer) * plane;
+    const bf16_t* vp = kp + plane;
+    int blk[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int bi = (kbase >> 4) + t;
+      const int b = (bi < a.kv.mbps && bi * 16 <= pos_max) ? a.kv.table[seq * a.kv.mbps + bi] : -1;
+      blk[t] = b < 0 ? 0 : b;
+      const bf16_t* kr = kp + ((size_t)(blk[t] * nkv + kvh) * 16 + c16) * HD + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[t][ks] = *(const u32x4*)(kr + 32 * ks);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];      // keys 32ks + 8g.. live in block 2ks + g/2
+      const bf16_t* vr = vp + ((size_t)(vblk * nkv + kvh) * HD + c16) * 16 + (g & 1) * 8;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) vf[ks][dt] = *(const u32x4*)(vr + dt * 256);
+    }
+  }
+  const float scale2 = a.scale * 1.4426950408889634f;
+  const int ntiles = (RG + 15) >> 4;
+  for (int rt = 0; rt < ntiles; ++rt) {
+    float mrow[4], lrow[4];
+    f32x4 oacc[DT];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { mrow[r] = -INFINITY; lrow[r] = 0.f; }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[dt] = f32x4{0, 0, 0, 0};
+    if (wlive) {
+      // Q fragments: A-operand row c16 = tile row 16 rt + c16 = (row j of the sequence, query head gq of the group)
+      SplitA qf[KS];
+      {
+        const int qr = 16 * rt + c16;
+        const bool qok = qr < RG;
+        const int j = qok ? qr / G : 0, gq = qok ? qr - j * G : 0;
+        const u32x4* qp = (const u32x4*)(a.q + ((size_t)(m_first + j) * a.nq + kvh * G + gq) * HD + g * 8);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          u32x4 x0 = u32x4{0u, 0u, 0u, 0u}, x1 = x0;
+          if (qok) { x0 = qp[8 * ks]; x1 = qp[8 * ks + 1]; }
+          qf[ks] = split_bf16(x0, x1);
+        }
+      }
+      f32x4 s[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        f32x4 z = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].lo, __builtin_bit_cast(bf16x8, kf[t][ks]), z, 0, 0, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].hi, __builtin_bit_cast(bf16x8, kf[t][ks]), z, 0, 0, 0);
+        s[t] = z;
+      }
+      // element (reg r, tile t) = (tile row 4g + r, key kbase + 16t + c16)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int qr = 16 * rt + 4 * g + r;
+        const int pos = qr < RG ? a.rows.pos[m_first + qr / G] : -1;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const bool ok = kbase + 16 * t + c16 <= pos;
+          s[t][r] = ok ? s[t][r] * scale2 : -INFINITY;
+          mx = fmaxf(mx, s[t][r]);
+        }
+        mx = row16_max(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float p = (s[t][r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[t][r] - mx);
+          Pw[uw][(4 * g + r) * 64 + 16 * t + c16] = p;
+          sum += p;
+        }
+        mrow[r] = mx;
+        lrow[r] = row16_sum(sum);
+      }
+      __builtin_amdgcn_wave_barrier();
+      // O = P V: P fragment row c16, keys 32ks + 8g..; V fragment dim 16dt + c16, same keys
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const u32x4* pp = (const u32x4*)(&Pw[uw][c16 * 64 + ks * 32 + g * 8]);
+        const SplitA pf = split_bf16(pp[0], pp[1]);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          const bf16x8 vv = __builtin_bit_cast(bf16x8, vf[ks][dt]);
+          oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.lo, vv, oacc[dt], 0, 0, 0);
+          oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.hi, vv, oacc[dt], 0, 0, 0);
+        }
+      }
+    }
+    // merge the four waves (ascending key order) and store the part's partial
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = 4 * g + r;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) MO[uw][row * HD + 16 * dt + c16] = oacc[dt][r];
+      if (c16 == 0) { ML[uw][row][0] = mrow[r]; ML[uw][row][1] = lrow[r]; }
+    }
+    __syncthreads();
+    {
+      const int row = tid >> 4, d0 = (tid & 15) * 4;
+      const int qr = 16 * rt + row;
+      if (qr < RG) {
+        const int j = qr / G, gq = qr - j * G;
+        const int m = m_first + j;
+        if (pbase <= a.rows.pos[m]) {                      // the row's own parts only (the combine reads no others)
+          float mx = -INFINITY;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) mx = fmaxf(mx, ML[w][row][0]);
+          float l = 0.f, o[HD / 16];
+#pragma unroll
+          for (int i = 0; i < HD / 16; ++i) o[i] = 0.f;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float mw = ML[w][row][0];
+            const float e = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);
+            l = fmaf(ML[w][row][1], e, l);
+#pragma unroll
+            for (int h = 0; h < HD / 64; ++h) {
+              const float4 x = *(const float4*)(&MO[w][row * HD + 64 * h + d0]);
+              o[4 * h] = fmaf(x.x, e, o[4 * h]); o[4 * h + 1] = fmaf(x.y, e, o[4 * h + 1]);
+              o[4 * h + 2] = fmaf(x.z, e, o[4 * h + 2]); o[4 * h + 3] = fmaf(x.w, e, o[4 * h + 3]);
+            }
+          }
+          const size_t pidx = ((size_t)m * a.nq + kvh * G + gq) * a.NC + part;
+#pragma unroll
+          for (int h = 0; h < HD / 64; ++h)
+            *(float4*)(a.o_part + pidx * HD + 64 * h + d0) = float4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]};
+          if ((tid & 15) == 0) { a.ml_part[pidx * 2] = mx; a.ml_part[pidx * 2 + 1] = l; }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// One wave per (row, query head): merge the row's part partials (base-2 maxima) in ascending part order.
+template <int HD, typename AT>
+__global__ void __launch_bounds__(WAVE) k_attn_combine_parts(AttnArgs a) {
+  const int m = blockIdx.x / a.nq, hq = blockIdx.x - m * a.nq;
+  const int lane = threadIdx.x;
+  const int np = a.rows.pos[m] / ATT_PART_KEYS + 1;
+  const size_t base = ((size_t)m * a.nq + hq) * a.NC;
+  float mx = -INFINITY;
+  for (int p = 0; p < np; ++p) mx = fmaxf(mx, a.ml_part[(base + p) * 2]);
+  float l = 0.f, o[HD / 64];
+#pragma unroll
+  for (int i = 0; i < HD / 64; ++i) o[i] = 0.f;
+#pragma unroll 4
+  for (int p = 0; p < np; ++p) {
+    const float mc = a.ml_part[(base + p) * 2];
+    const float w = (mc == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mc - mx);
+    l = fmaf(a.ml_part[(base + p) * 2 + 1], w, l);
+#pragma unroll
+    for (int i = 0; i < HD / 64; ++i) o[i] = fmaf(a.o_part[(base + p) * HD + lane + i * WAVE], w, o[i]);
+  }
+  typename AT::T* out = (typename AT::T*)a.out + (size_t)m * a.nq * HD + hq * HD;
+#pragma unroll
+  for (int i = 0; i < HD / 64; ++i) AT::st(out + lane + i * WAVE, o[i] / l);
+}
+
 }  // namespace ssd

@@ -117,6 +117,54 @@ __device__ __forceinline__ size_t kv_offset(const KvView& kv, int layer, int whi
   return ((((size_t)(layer * 2 + which) * kv.n_blocks + blk) * kv.nkv + head) * kv.bt + tok) * (size_t)kv.hd;
 }
 
+// All-reduce over the 16 lanes of a DPP row (lanes 16k .. 16k+15) with data-parallel primitives instead of LDS
+// shuffles: pairs, quads (quad_perm), half rows (row_half_mirror), rows (row_mirror).  Every step combines a lane's
+// value with the value of a lane of the complementary group, so all 16 lanes end with bit-identical results.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<0xB1>(v);       // quad_perm [1,0,3,2]
+  v += dpp_f<0x4E>(v);       // quad_perm [2,3,0,1]
+  v += dpp_f<0x141>(v);      // row_half_mirror
+  v += dpp_f<0x140>(v);      // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  v = fmaxf(v, dpp_f<0x141>(v));
+  v = fmaxf(v, dpp_f<0x140>(v));
+  return v;
+}
+
+// --------------------------------------------------------------------------------------- bf16 / MFMA
+// Activations are kept in fp32 and fed to the matrix core as a sum of two bf16 values, x = hi + lo with
+// hi = the upper 16 bits of x and lo = bf16(x - hi): two MFMAs per weight fragment instead of one, which
+// the weight-streaming regime does not notice, and activation rounding (2^-17 instead of 2^-9 relative)
+// stops being the largest error of the bf16 path.  Weights are bf16 as stored.
+struct SplitA {
+  bf16x8 hi, lo;
+};
+__device__ __forceinline__ SplitA split_bf16(const u32x4 a, const u32x4 b) {
+  const uint32_t x[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t u0 = x[2 * i], u1 = x[2 * i + 1];
+    const uint32_t h0 = u0 & 0xFFFF0000u, h1 = u1 & 0xFFFF0000u;
+    const float r0 = __uint_as_float(u0) - __uint_as_float(h0);       // exact
+    const float r1 = __uint_as_float(u1) - __uint_as_float(h1);
+    h[i] = (h0 >> 16) | h1;
+    l[i] = (uint32_t)f_to_bf16(r0) | ((uint32_t)f_to_bf16(r1) << 16);
+  }
+  SplitA s;
+  s.hi = __builtin_bit_cast(bf16x8, u32x4{h[0], h[1], h[2], h[3]});
+  s.lo = __builtin_bit_cast(bf16x8, u32x4{l[0], l[1], l[2], l[3]});
+  return s;
+}
+
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Make `seq` own the blocks that cover `tokens` positions (one thread).

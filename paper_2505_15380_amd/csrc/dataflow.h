@@ -104,28 +104,6 @@ __device__ __forceinline__ uint32_t split_payload(float x) {
   return (h >> 16) | ((uint32_t)f_to_bf16(x - __uint_as_float(h)) << 16);
 }
 
-// All-reduce over the 16 lanes of a DPP row (lanes 16k .. 16k+15) with data-parallel primitives instead of LDS
-// shuffles: pairs, quads (quad_perm), half rows (row_half_mirror), rows (row_mirror).  Every step combines a lane's
-// value with the value of a lane of the complementary group, so all 16 lanes end with bit-identical results.
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float row16_sum(float v) {
-  v += dpp_f<0xB1>(v);       // quad_perm [1,0,3,2]
-  v += dpp_f<0x4E>(v);       // quad_perm [2,3,0,1]
-  v += dpp_f<0x141>(v);      // row_half_mirror
-  v += dpp_f<0x140>(v);      // row_mirror
-  return v;
-}
-__device__ __forceinline__ float row16_max(float v) {
-  v = fmaxf(v, dpp_f<0xB1>(v));
-  v = fmaxf(v, dpp_f<0x4E>(v));
-  v = fmaxf(v, dpp_f<0x141>(v));
-  v = fmaxf(v, dpp_f<0x140>(v));
-  return v;
-}
-
 // A workgroup that arrives at a phase long before its operands would poll them the whole time, and the polls of all
 // such workgroups load the fabric that the producers' stores travel through.  After a first failed flight a wave
 // therefore watches one word of the operands of the PRECEDING phase (one hand-over earlier) with a single

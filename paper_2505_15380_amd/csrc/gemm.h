@@ -122,32 +122,6 @@ __device__ __forceinline__ void gemm_reduce_tile(const GemmArgs& g, float (*red)
   gemm_epilogue<EPI, AT, KVT>(g, t0, t1, split, mt * 16 + (tid >> 4), tid & 15, v0, v1);
 }
 
-// --------------------------------------------------------------------------------------- bf16 / MFMA
-// Activations are kept in fp32 and fed to the matrix core as a sum of two bf16 values, x = hi + lo with
-// hi = the upper 16 bits of x and lo = bf16(x - hi): two MFMAs per weight fragment instead of one, which
-// the weight-streaming regime does not notice, and activation rounding (2^-17 instead of 2^-9 relative)
-// stops being the largest error of the bf16 path.  Weights are bf16 as stored.
-struct SplitA {
-  bf16x8 hi, lo;
-};
-__device__ __forceinline__ SplitA split_bf16(const u32x4 a, const u32x4 b) {
-  const uint32_t x[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  uint32_t h[4], l[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t u0 = x[2 * i], u1 = x[2 * i + 1];
-    const uint32_t h0 = u0 & 0xFFFF0000u, h1 = u1 & 0xFFFF0000u;
-    const float r0 = __uint_as_float(u0) - __uint_as_float(h0);       // exact
-    const float r1 = __uint_as_float(u1) - __uint_as_float(h1);
-    h[i] = (h0 >> 16) | h1;
-    l[i] = (uint32_t)f_to_bf16(r0) | ((uint32_t)f_to_bf16(r1) << 16);
-  }
-  SplitA s;
-  s.hi = __builtin_bit_cast(bf16x8, u32x4{h[0], h[1], h[2], h[3]});
-  s.lo = __builtin_bit_cast(bf16x8, u32x4{l[0], l[1], l[2], l[3]});
-  return s;
-}
-
 // grid.x = work items (tile pairs x global splits).  MT = 16-row tiles of M.  A is fp32 [M][lda].
 template <int MT, int EPI, typename KVT>
 __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {

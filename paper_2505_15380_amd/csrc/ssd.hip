@@ -11,6 +11,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "attention.h"
@@ -308,6 +309,7 @@ struct ssd_kv {
   u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
+  bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
   // host
   int32_t* mirror_host;
@@ -452,6 +454,10 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
     const char* env = getenv("SSD_FORWARD");
     kv->dataflow = !(env && strcmp(env, "barrier") == 0);
   }
+  {
+    const char* env = getenv("SSD_ATTN");
+    kv->attn_mfma = !(env && strcmp(env, "valu") == 0);
+  }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
   return SSD_OK;
@@ -521,7 +527,17 @@ static int pick_splits(int K, int npairs) {
 }
 
 template <typename DT, int HD>
-static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, hipStream_t st) {
+static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, bool mfma, hipStream_t st) {
+  if constexpr (std::is_same<DT, BF16>::value && (HD == 64 || HD == 128)) {
+    if (mfma && a.kv.bt == 16) {                          // keys and values as matrix-core fragments, 256-key parts
+      const int nparts = cdiv(nchunks * ATT_CHUNK, ATT_PART_KEYS);
+      hipLaunchKernelGGL((k_attn_part_mfma<HD>), dim3(nparts, nkv, B), dim3(BLOCK), 0, st, a);
+      LAUNCH_CHECK();
+      hipLaunchKernelGGL((k_attn_combine_parts<HD, F32>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
+      LAUNCH_CHECK();
+      return SSD_OK;
+    }
+  }
   hipLaunchKernelGGL((k_attn_chunk<HD, DT>), dim3(nchunks, nkv, B), dim3(BLOCK), 0, st, a);
   LAUNCH_CHECK();
   hipLaunchKernelGGL((k_attn_combine<HD, F32>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
@@ -669,9 +685,9 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
     a.o_part = kv->o_part; a.ml_part = kv->ml_part; a.NC = kv->NC; a.out = kv->attn;
     {
       ProfScope ps(PROF_ATTN, st);
-      if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, st);
-      else if (hd == 64) rc = launch_attn<DT, 64>(a, nchunks, nkv, B, M, st);
-      else rc = launch_attn<DT, 128>(a, nchunks, nkv, B, M, st);
+      if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, kv->attn_mfma, st);
+      else if (hd == 64) rc = launch_attn<DT, 64>(a, nchunks, nkv, B, M, kv->attn_mfma, st);
+      else rc = launch_attn<DT, 128>(a, nchunks, nkv, B, M, kv->attn_mfma, st);
     }
     if (rc) return rc;
 

@@ -150,6 +150,32 @@ def test_batched_ragged_verify_parity(workload, tol):
     assert len({tuple(n) for n in ns}) > 1 and any(len(set(n)) > 1 for n in ns)
 
 
+def test_batched_verify_beyond_one_row_tile_uses_matrix_core_attention():
+    """Five ragged sequences x (K+1 = 5) rows = 25 rows: more than the persistent kernels take, so every operator is
+    its own launch and attention runs as 256-key parts on the matrix cores.  Lengths put new positions on both sides
+    of a part boundary (250 -> 256), in a second and third part, and inside the first chunk."""
+    from tests.parity import Pair, verify_parity_step
+    wl = si.workload("mini")
+    shape = si.model_shape(wl["target"])
+    B, K, steps = 5, 4, 3
+    lens = [23, 250, 300, 515, 64]
+    cap = max(lens) + steps * (K + 1) + 20
+    pair = Pair(wl["target"], wl["seeds"]["target"], cap, max_seqs=B, max_rows=8, block_tokens=16)
+    for b in range(B):
+        pair.prefill(b, si.make_prefix(shape, 3, lens[b] - 3, 700 + b))
+    rng = np.random.default_rng(6)
+    cfg = dict(beta=0.2, temperature=1.0, top_k=0, greedy=False, seed=99)
+    worst = 0.0
+    for s in range(steps):
+        res = verify_parity_step(pair, cfg, K, s, rng, 2e-2, 2e-2, seqs=tuple(range(B)))
+        assert pair.kv.last_forward_path() == 1
+        worst = max(worst, max(r["dlogits"] for r in res))
+        for b in range(B):
+            pair.check_state(b, 2e-2, layers=[shape["n_layers"] - 1])
+        pair.check_free_stack()
+    assert 0 < worst < 2e-2
+
+
 def test_rollback_and_reverify():
     """After a verification that rejected drafts, positions below the new length are untouched, stale positions
     are overwritten by the next call, and an explicit rollback frees whole blocks in the documented order."""
