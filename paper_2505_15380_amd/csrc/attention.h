@@ -129,23 +129,54 @@ __global__ void __launch_bounds__(WAVE) k_attn_combine(AttnArgs a) {
 
 // ------------------------------------------------------------------------------------------------ matrix-core variant
 // The same operation for bf16 caches with 16-token blocks and head_dim 64 or 128, for launches with many rows
-// (batched verification).  Work item = (part of 256 key positions, kv head, sequence); wave w of the workgroup
-// takes keys [256 part + 64 w, +64) and reads them ONCE, as MFMA operand fragments straight from the cache: a
-// K fragment is 8 consecutive dims of one cached key row, a V fragment 8 consecutive tokens of one dim of the
-// token-minor value layout.  The query rows that share the keys - R rows of the sequence x the G query heads of
-// the group - are walked in tiles of 16: S = Q K^T (queries as hi + lo bf16, so they are not rounded), a masked
-// softmax per row over the wave's 64 keys in the base-2 domain, O = P V with P split the same way.  The four
-// waves' partials are merged in ascending key order through LDS and stored as one partial per (row, head, part);
-// k_attn_combine_parts merges the parts in ascending order.  Parts are cut at absolute positions, so a row's
-// bits do not depend on which other rows share the launch.
+// (batched verification).  Work item = (part of 256 key positions, kv head, sequence).  The query rows that share
+// the keys - R rows of the sequence x the G query heads of the group - form tiles of 16; wave w of the workgroup
+// takes tiles w, w+4, .. and walks the part's four 64-key chunks in ascending order with a running (max, sum,
+// weighted values) per row, so no partial ever crosses waves.  Keys and values are read once, as MFMA operand
+// fragments straight from the cache (a K fragment is 8 consecutive dims of one cached key row, a V fragment 8
+// consecutive tokens of one dim of the token-minor value layout): wave w loads the fragments of chunk w and parks
+// them in LDS in fragment order, so the whole part is in flight at once and every wave then reads any chunk with
+// conflict-free 16-byte LDS reads.  S = Q K^T with the queries as hi + lo bf16, a masked softmax in the base-2
+// domain, O = P V with P split the same way.  The result is one partial per (row, head, part);
+// k_attn_combine_parts merges the parts in ascending order.  Parts and chunks are cut at absolute positions, so a
+// row's bits do not depend on which other rows share the launch.
 constexpr int ATT_PART_KEYS = 256;
 
 template <int HD>
+struct KVFrag {
+  u32x4 kf[4][HD / 32], vf[2][HD / 16];
+};
+
+// Fragments of keys [kbase, kbase + 64) of (seq, kvh); masked keys may read any valid block.
+template <int HD>
+__device__ __forceinline__ void attn_load_chunk(const AttnArgs& a, const bf16_t* kp, const bf16_t* vp, int seq, int kvh,
+                                                int kbase, int pos_max, int g, int c16, KVFrag<HD>& f) {
+  const int nkv = a.kv.nkv;
+  int blk[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int bi = (kbase >> 4) + t;
+    const int b = (bi < a.kv.mbps && bi * 16 <= pos_max) ? a.kv.table[seq * a.kv.mbps + bi] : -1;
+    blk[t] = b < 0 ? 0 : b;
+    const bf16_t* kr = kp + ((size_t)(blk[t] * nkv + kvh) * 16 + c16) * HD + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < HD / 32; ++ks) f.kf[t][ks] = *(const u32x4*)(kr + 32 * ks);
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int b0 = blk[2 * ks], b1 = blk[2 * ks + 1];
+    const int vblk = (g >> 1) ? b1 : b0;                              // keys 32ks + 8g.. live in block 2ks + g/2
+    const bf16_t* vr = vp + ((size_t)(vblk * nkv + kvh) * HD + c16) * 16 + (g & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt) f.vf[ks][dt] = *(const u32x4*)(vr + dt * 256);
+  }
+}
+
+template <int HD>
 __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
-  constexpr int KS = HD / 32, DT = HD / 16;
+  constexpr int KS = HD / 32, DT = HD / 16, NF = 4 * KS + 2 * DT;     // fragments of a chunk: 16 (HD 64) or 32 (HD 128)
   __shared__ __attribute__((aligned(16))) float Pw[4][16 * 64];
-  __shared__ __attribute__((aligned(16))) float MO[4][16 * HD];
-  __shared__ float ML[4][16][2];
+  __shared__ u32x4 KV[4][NF][64];                        // the part's fragments, [chunk][fragment][lane]
   const int part = blockIdx.x, kvh = blockIdx.y, brel = blockIdx.z;
   const int seq = a.rows.seq0 + brel;
   const int R = a.rows.R, nkv = a.kv.nkv, G = a.nq / nkv, RG = R * G;
@@ -155,147 +186,129 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
   if (pbase > pos_max) return;                           // no row of this sequence reaches the part
   const int tid = threadIdx.x, lane = tid & 63, uw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c16 = lane & 15;
-  const int kbase = pbase + 64 * uw;
-  const bool wlive = kbase <= pos_max;                   // wave-uniform
-
-  // fragments of the wave's 64 keys and values (masked keys may read any valid block)
-  u32x4 kf[4][KS], vf[2][DT];
-  if (wlive) {
+  const int nch = min(4, ((pos_max - pbase) >> 6) + 1);  // chunks of the part that some row reaches
+  // wave w brings chunk w into LDS: every fragment load of the part is in flight at once
+  if (uw < nch) {
     const size_t plane = (size_t)a.kv.n_blocks * nkv * 16 * HD;
     const bf16_t* kp = (const bf16_t*)a.kv.pool + (size_t)(2 * a.layer) * plane;
-    const bf16_t* vp = kp + plane;
-    int blk[4];
+    KVFrag<HD> f;
+    attn_load_chunk<HD>(a, kp, kp + plane, seq, kvh, pbase + 64 * uw, pos_max, g, c16, f);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int bi = (kbase >> 4) + t;
-      const int b = (bi < a.kv.mbps && bi * 16 <= pos_max) ? a.kv.table[seq * a.kv.mbps + bi] : -1;
-      blk[t] = b < 0 ? 0 : b;
-      const bf16_t* kr = kp + ((size_t)(blk[t] * nkv + kvh) * 16 + c16) * HD + g * 8;
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[t][ks] = *(const u32x4*)(kr + 32 * ks);
-    }
+      for (int ks = 0; ks < KS; ++ks) KV[uw][t * KS + ks][lane] = f.kf[t][ks];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];      // keys 32ks + 8g.. live in block 2ks + g/2
-      const bf16_t* vr = vp + ((size_t)(vblk * nkv + kvh) * HD + c16) * 16 + (g & 1) * 8;
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vf[ks][dt] = *(const u32x4*)(vr + dt * 256);
-    }
+      for (int dt = 0; dt < DT; ++dt) KV[uw][4 * KS + ks * DT + dt][lane] = f.vf[ks][dt];
   }
   const float scale2 = a.scale * 1.4426950408889634f;
   const int ntiles = (RG + 15) >> 4;
-  for (int rt = 0; rt < ntiles; ++rt) {
+  float* P = Pw[uw];
+  // Q fragments of the wave's first tile travel while the keys do
+  auto load_q = [&](int rt, u32x4 (&x)[KS][2]) {
+    const int qr = 16 * rt + c16;                        // A-operand row c16 = (row j of the sequence, query head gq)
+    const bool qok = qr < RG;
+    const int j = qok ? qr / G : 0, gq = qok ? qr - j * G : 0;
+    const u32x4* qp = (const u32x4*)(a.q + ((size_t)(m_first + j) * a.nq + kvh * G + gq) * HD + g * 8);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      x[ks][0] = u32x4{0u, 0u, 0u, 0u};
+      x[ks][1] = x[ks][0];
+      if (qok) { x[ks][0] = qp[8 * ks]; x[ks][1] = qp[8 * ks + 1]; }
+    }
+  };
+  auto load_pos = [&](int rt, int (&pos)[4]) {           // of accumulator rows 4g + r; -1: not a row
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int qr = 16 * rt + 4 * g + r;
+      pos[r] = qr < RG ? a.rows.pos[m_first + qr / G] : -1;
+    }
+  };
+  u32x4 qraw[KS][2];
+  int pos[4];
+  if (uw < ntiles) { load_q(uw, qraw); load_pos(uw, pos); }
+  __syncthreads();
+  for (int rt = uw; rt < ntiles; rt += 4) {
+    if (rt != uw) { load_q(rt, qraw); load_pos(rt, pos); }
+    SplitA qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = split_bf16(qraw[ks][0], qraw[ks][1]);
     float mrow[4], lrow[4];
     f32x4 oacc[DT];
 #pragma unroll
     for (int r = 0; r < 4; ++r) { mrow[r] = -INFINITY; lrow[r] = 0.f; }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) oacc[dt] = f32x4{0, 0, 0, 0};
-    if (wlive) {
-      // Q fragments: A-operand row c16 = tile row 16 rt + c16 = (row j of the sequence, query head gq of the group)
-      SplitA qf[KS];
-      {
-        const int qr = 16 * rt + c16;
-        const bool qok = qr < RG;
-        const int j = qok ? qr / G : 0, gq = qok ? qr - j * G : 0;
-        const u32x4* qp = (const u32x4*)(a.q + ((size_t)(m_first + j) * a.nq + kvh * G + gq) * HD + g * 8);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          u32x4 x0 = u32x4{0u, 0u, 0u, 0u}, x1 = x0;
-          if (qok) { x0 = qp[8 * ks]; x1 = qp[8 * ks + 1]; }
-          qf[ks] = split_bf16(x0, x1);
-        }
-      }
+    for (int c = 0; c < nch; ++c) {
+      const int kbase = pbase + 64 * c;
       f32x4 s[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kf[ks] = __builtin_bit_cast(bf16x8, KV[c][t * KS + ks][lane]);
         f32x4 z = f32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].lo, __builtin_bit_cast(bf16x8, kf[t][ks]), z, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].lo, kf[ks], z, 0, 0, 0);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].hi, __builtin_bit_cast(bf16x8, kf[t][ks]), z, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks].hi, kf[ks], z, 0, 0, 0);
         s[t] = z;
       }
       // element (reg r, tile t) = (tile row 4g + r, key kbase + 16t + c16)
+      float alpha[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int qr = 16 * rt + 4 * g + r;
-        const int pos = qr < RG ? a.rows.pos[m_first + qr / G] : -1;
         float mx = -INFINITY;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          const bool ok = kbase + 16 * t + c16 <= pos;
+          const bool ok = kbase + 16 * t + c16 <= pos[r];
           s[t][r] = ok ? s[t][r] * scale2 : -INFINITY;
           mx = fmaxf(mx, s[t][r]);
         }
-        mx = row16_max(mx);
+        const float mnew = fmaxf(mrow[r], row16_max(mx));
+        alpha[r] = (mrow[r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mrow[r] - mnew);
         float sum = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          const float p = (s[t][r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[t][r] - mx);
-          Pw[uw][(4 * g + r) * 64 + 16 * t + c16] = p;
+          const float p = (s[t][r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[t][r] - mnew);
+          P[(4 * g + r) * 64 + 16 * t + c16] = p;
           sum += p;
         }
-        mrow[r] = mx;
-        lrow[r] = row16_sum(sum);
+        mrow[r] = mnew;
+        lrow[r] = fmaf(lrow[r], alpha[r], row16_sum(sum));
       }
       __builtin_amdgcn_wave_barrier();
-      // O = P V: P fragment row c16, keys 32ks + 8g..; V fragment dim 16dt + c16, same keys
+      // O = alpha O + P V: P fragment row c16, keys 32ks + 8g..; V fragment dim 16dt + c16, same keys
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) oacc[dt][r] *= alpha[r];
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const u32x4* pp = (const u32x4*)(&Pw[uw][c16 * 64 + ks * 32 + g * 8]);
+        const u32x4* pp = (const u32x4*)(P + c16 * 64 + ks * 32 + g * 8);
         const SplitA pf = split_bf16(pp[0], pp[1]);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-          const bf16x8 vv = __builtin_bit_cast(bf16x8, vf[ks][dt]);
+          const bf16x8 vv = __builtin_bit_cast(bf16x8, KV[c][4 * KS + ks * DT + dt][lane]);
           oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.lo, vv, oacc[dt], 0, 0, 0);
           oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.hi, vv, oacc[dt], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_wave_barrier();                   // P is rewritten by the next chunk
     }
-    // merge the four waves (ascending key order) and store the part's partial
+    // the part's partial of every row that reaches the part (the combine reads no others)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int row = 4 * g + r;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) MO[uw][row * HD + 16 * dt + c16] = oacc[dt][r];
-      if (c16 == 0) { ML[uw][row][0] = mrow[r]; ML[uw][row][1] = lrow[r]; }
-    }
-    __syncthreads();
-    {
-      const int row = tid >> 4, d0 = (tid & 15) * 4;
-      const int qr = 16 * rt + row;
-      if (qr < RG) {
+      const int qr = 16 * rt + 4 * g + r;
+      if (pbase <= pos[r]) {
         const int j = qr / G, gq = qr - j * G;
-        const int m = m_first + j;
-        if (pbase <= a.rows.pos[m]) {                      // the row's own parts only (the combine reads no others)
-          float mx = -INFINITY;
+        const size_t pidx = ((size_t)(m_first + j) * a.nq + kvh * G + gq) * a.NC + part;
 #pragma unroll
-          for (int w = 0; w < 4; ++w) mx = fmaxf(mx, ML[w][row][0]);
-          float l = 0.f, o[HD / 16];
-#pragma unroll
-          for (int i = 0; i < HD / 16; ++i) o[i] = 0.f;
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const float mw = ML[w][row][0];
-            const float e = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mx);
-            l = fmaf(ML[w][row][1], e, l);
-#pragma unroll
-            for (int h = 0; h < HD / 64; ++h) {
-              const float4 x = *(const float4*)(&MO[w][row * HD + 64 * h + d0]);
-              o[4 * h] = fmaf(x.x, e, o[4 * h]); o[4 * h + 1] = fmaf(x.y, e, o[4 * h + 1]);
-              o[4 * h + 2] = fmaf(x.z, e, o[4 * h + 2]); o[4 * h + 3] = fmaf(x.w, e, o[4 * h + 3]);
-            }
-          }
-          const size_t pidx = ((size_t)m * a.nq + kvh * G + gq) * a.NC + part;
-#pragma unroll
-          for (int h = 0; h < HD / 64; ++h)
-            *(float4*)(a.o_part + pidx * HD + 64 * h + d0) = float4{o[4 * h], o[4 * h + 1], o[4 * h + 2], o[4 * h + 3]};
-          if ((tid & 15) == 0) { a.ml_part[pidx * 2] = mx; a.ml_part[pidx * 2 + 1] = l; }
-        }
+        for (int dt = 0; dt < DT; ++dt) a.o_part[pidx * HD + 16 * dt + c16] = oacc[dt][r];
+        if (c16 == 0) { a.ml_part[pidx * 2] = mrow[r]; a.ml_part[pidx * 2 + 1] = lrow[r]; }
       }
     }
-    __syncthreads();
   }
 }
 

@@ -15,11 +15,13 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 __device__ __forceinline__ float bf16_to_f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ __forceinline__ bf16_t f_to_bf16(float f) {   // round to nearest even (finite inputs)
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// Round to nearest even with the gfx950 conversion instruction (two values per instruction).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+__device__ __forceinline__ uint32_t f2_to_bf16x2(float lo, float hi) {      // bits [15:0] = bf16(lo), [31:16] = bf16(hi)
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t f_to_bf16(float f) { return (bf16_t)(f2_to_bf16x2(f, 0.f) & 0xFFFFu); }
 
 // Storage types of activations / weights / KV: load as float, store from float.
 struct F32 {
@@ -157,7 +159,7 @@ __device__ __forceinline__ SplitA split_bf16(const u32x4 a, const u32x4 b) {
     const float r0 = __uint_as_float(u0) - __uint_as_float(h0);       // exact
     const float r1 = __uint_as_float(u1) - __uint_as_float(h1);
     h[i] = (h0 >> 16) | h1;
-    l[i] = (uint32_t)f_to_bf16(r0) | ((uint32_t)f_to_bf16(r1) << 16);
+    l[i] = f2_to_bf16x2(r0, r1);
   }
   SplitA s;
   s.hi = __builtin_bit_cast(bf16x8, u32x4{h[0], h[1], h[2], h[3]});

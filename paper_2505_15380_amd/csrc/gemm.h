@@ -122,7 +122,8 @@ __device__ __forceinline__ void gemm_reduce_tile(const GemmArgs& g, float (*red)
   gemm_epilogue<EPI, AT, KVT>(g, t0, t1, split, mt * 16 + (tid >> 4), tid & 15, v0, v1);
 }
 
-// grid.x = work items (tile pairs x global splits).  MT = 16-row tiles of M.  A is fp32 [M][lda].
+// grid.x = work items (tile pairs x global splits); grid.y = groups of MT 16-row tiles of M (a workgroup reads its
+// weights once for its MT row tiles; more groups = more workgroups for the same weights).  A is fp32 [M][lda].
 template <int MT, int EPI, typename KVT>
 __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
   __shared__ float red[4][2][256];
@@ -132,6 +133,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
   const bool has1 = (EPI != EPI_PARTIAL) || (t1 < ntiles);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int KT = g.K >> 5;
+  const int mt0 = blockIdx.y * MT;
   // k-tiles of this workgroup, then of this wave (contiguous ranges, earlier ranges get the remainder)
   const int per_s = KT / g.gs, rem_s = KT - per_s * g.gs;
   const int wg_b = split * per_s + min(split, rem_s), wg_n = per_s + (split < rem_s ? 1 : 0);
@@ -158,7 +160,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
     }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int row = mt * 16 + arow;
+      const int row = (mt0 + mt) * 16 + arow;
       u32x4 a[U][2];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -186,7 +188,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
     const bf16x8 bv1 = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(w1 + (size_t)kt * 64));
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const int row = mt * 16 + arow;
+      const int row = (mt0 + mt) * 16 + arow;
       u32x4 a0 = u32x4{0u, 0u, 0u, 0u}, a1 = u32x4{0u, 0u, 0u, 0u};
       if (row < g.M) {
         const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + kt * 32 + akoff);
@@ -204,7 +206,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
   const int obase = ((lane >> 4) * 4) * 16 + (lane & 15);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    if (mt * 16 < g.M) {
+    if ((mt0 + mt) * 16 < g.M) {
       __syncthreads();
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -212,7 +214,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
         red[wave][1][obase + r * 16] = acc[mt][1][r];
       }
       __syncthreads();
-      gemm_reduce_tile<EPI, F32, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt);
+      gemm_reduce_tile<EPI, F32, KVT>(g, red, t0, has1 ? t1 : ntiles, split, mt0 + mt);
     }
   }
 }

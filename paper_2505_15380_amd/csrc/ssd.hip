@@ -510,8 +510,7 @@ static int launch_gemm(const ssd_model* m, GemmArgs g, int items, hipStream_t st
     const int MT = cdiv(g.M, 16);
     if (MT <= 1) hipLaunchKernelGGL((k_gemm_bf16<1, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
     else if (MT <= 2) hipLaunchKernelGGL((k_gemm_bf16<2, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
-    else if (MT <= 4) hipLaunchKernelGGL((k_gemm_bf16<4, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
-    else hipLaunchKernelGGL((k_gemm_bf16<8, EPI, BF16>), dim3(items), dim3(BLOCK), 0, st, g);
+    else hipLaunchKernelGGL((k_gemm_bf16<2, EPI, BF16>), dim3(items, cdiv(MT, 2)), dim3(BLOCK), 0, st, g);
   } else {
     hipLaunchKernelGGL((k_gemm_f32<EPI, F32>), dim3(items), dim3(BLOCK), 0, st, g);
   }
@@ -665,8 +664,10 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   memset(&g0, 0, sizeof g0);
   g0.M = M; g0.kv = kv->v; g0.rows = rows; g0.nq = nq; g0.rope = m->rope;
   const size_t part_stride = (size_t)M * d;
-  const int gs_o = pick_splits(nqd, cdiv(cdiv(d, 16), 2));
-  const int gs_d = pick_splits(c.d_ffn, cdiv(cdiv(d, 16), 2));
+  // k-splits fill the machine when there is one group of row tiles; with more groups (see launch_gemm) the groups do
+  const int row_groups = m->c.dtype == SSD_DTYPE_BF16 && M > 32 ? cdiv(cdiv(M, 16), 2) : 1;
+  const int gs_o = std::max(1, pick_splits(nqd, cdiv(cdiv(d, 16), 2)) / row_groups);
+  const int gs_d = std::max(1, pick_splits(c.d_ffn, cdiv(cdiv(d, 16), 2)) / row_groups);
   int n_part = 0;
   int rc;
   for (int l = 0; l < c.n_layers; ++l) {
