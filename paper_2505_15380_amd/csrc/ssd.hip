@@ -309,6 +309,7 @@ struct ssd_kv {
   u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
+  bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared gate/up kernel (SSD_GEMM=narrow: the generic one)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
   // host
@@ -457,6 +458,8 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   {
     const char* env = getenv("SSD_ATTN");
     kv->attn_mfma = !(env && strcmp(env, "valu") == 0);
+    env = getenv("SSD_GEMM");
+    kv->gemm_wide = !(env && strcmp(env, "narrow") == 0);
   }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
@@ -704,7 +707,28 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
 
     g = g0;                                                // gate / up + SwiGLU
     g.A = kv->xn; g.lda = d; g.W0 = L.wgate; g.W1 = L.wup; g.N = c.d_ffn; g.K = d; g.gs = 1; g.act = kv->act;
-    { ProfScope ps(PROF_GATEUP, st); rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st); }
+    {
+      ProfScope ps(PROF_GATEUP, st);
+      // many rows: row tiles x 8 column-tile pairs per workgroup, activations shared through LDS (see gemm.h)
+      const int mtw = (size_t)2 * 16 * d * 4 <= (size_t)WIDE_LDS_BYTES ? 2 : 1;
+      if (m->c.dtype == SSD_DTYPE_BF16 && M > 32 && kv->gemm_wide && (size_t)mtw * 16 * d * 4 <= (size_t)WIDE_LDS_BYTES) {
+        const dim3 grid(8 * cdiv(cdiv(cdiv(c.d_ffn, 16), WIDE_WAVES), 8) * cdiv(cdiv(M, 16), mtw));   // see the kernel's index map
+        const size_t lds = (size_t)mtw * 16 * d * 4;
+        static const hipError_t lds_ok = [] {               // more than 64 KB of dynamic LDS is opt-in, once per process
+          hipError_t e = hipFuncSetAttribute((const void*)k_gemm_swiglu_wide<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
+          if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)k_gemm_swiglu_wide<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
+          return e;
+        }();
+        if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
+        if (mtw == 2) hipLaunchKernelGGL((k_gemm_swiglu_wide<2>), grid, dim3(WIDE_WAVES * 64), lds, st, g);
+        else hipLaunchKernelGGL((k_gemm_swiglu_wide<1>), grid, dim3(WIDE_WAVES * 64), lds, st, g);
+        LAUNCH_CHECK();
+        rc = SSD_OK;
+      } else {
+        rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st);
+      }
+    }
     if (rc) return rc;
 
     g = g0;                                                // down projection -> k-split partials
