@@ -219,86 +219,108 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
   }
 }
 
-// -------------------------------------------------------------------------------------- many rows: gate / up
+// -------------------------------------------------------------------------------------- many rows
 // With several row tiles the decomposition above re-reads the activations once per pair of column tiles, and that
-// traffic, not the weights, sets the time of the widest operator.  Here a workgroup of 8 waves takes MTW row tiles
-// x 8 column-tile pairs: the rows' activations are split into hi + lo bf16 once, parked in LDS in A-fragment order
-// (whole k range: MTW * 16 * K * 4 bytes), and every wave runs its own pair over the full k range against them, so
-// nothing is reduced across waves.  Accumulation order of an element: k ascending, lo before hi per k-tile.
+// traffic, not the weights, sets the time of the wide operators.  Here a workgroup of 8 waves takes MTW row tiles
+// x 8 column-tile pairs (x one k-slice for the operators whose output is k-split partials): the rows' activations
+// are split into hi + lo bf16 once per workgroup and parked in LDS in A-fragment order, a chunk of KC k-tiles at a
+// time (MTW * KC * 2 KB), and every wave runs its own pair over the whole k range of the workgroup against them,
+// so nothing is reduced across waves.  Weight fragments are prefetched U k-tiles ahead, across chunk boundaries,
+// so they travel while the next chunk is staged.  Accumulation order of an element: k ascending, lo before hi.
 constexpr int WIDE_WAVES = 8;
 constexpr int WIDE_LDS_BYTES = 128 * 1024;
+constexpr int WIDE_MAX_MTW = 4;
 
-template <int MTW>
-__global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_swiglu_wide(GemmArgs g) {
-  extern __shared__ u32x4 afrag[];                        // [(mt * KT + kt) * 2 + {hi, lo}][lane]
+struct WideArgs {
+  int KC;            // k-tiles per staged chunk (multiple of 4, MTW * KC * 2048 <= WIDE_LDS_BYTES)
+  int slice_kt;      // k-tiles per workgroup (multiple of 4; the whole k range for the SwiGLU epilogue)
+  int n_slices, n_rowg, n_colg;
+};
+
+template <int MTW, int EPI>
+__global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideArgs wa) {
+  extern __shared__ u32x4 afrag[];                        // [(mt * KC + kt in chunk) * 2 + {hi, lo}][lane]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int KT = g.K >> 5;
-  // Workgroups are dealt to the 8 XCDs round-robin by their index; the row groups of one column group take indices
-  // that differ by 8, so they run on one XCD, close in time, and all but the first find the weights in its L2.
+  const int KT = g.K >> 5, KC = wa.KC;
+  // Workgroups are dealt to the 8 XCDs round-robin by their index; the row groups of one (column group, slice) take
+  // indices that differ by 8, so they run on one XCD, close in time, and all but the first find the weights in its L2.
   const int ntiles = (g.N + 15) >> 4;
-  const int n_rowg = ((g.M + 15) / 16 + MTW - 1) / MTW;
   const int xk = blockIdx.x >> 3;
-  const int colg = (xk / n_rowg) * 8 + (blockIdx.x & 7);
-  const int mt0 = (xk % n_rowg) * MTW;
-  if (colg * WIDE_WAVES >= ntiles) return;
-  const int t = colg * WIDE_WAVES + wave;                 // column tile of gate and of up
-  const bool live = t < ntiles;
-  const u32x4* w0 = (const u32x4*)g.W0 + (size_t)(live ? t : 0) * KT * 64 + lane;
-  const u32x4* w1 = (const u32x4*)g.W1 + (size_t)(live ? t : 0) * KT * 64 + lane;
-  constexpr int U = 4;                                    // k-tiles of weights in flight per wave (x 2 KB), issued before
-  u32x4 b0[U], b1[U];                                     // the activations are staged so that both travel together
+  const int per_col = wa.n_rowg * wa.n_slices;
+  const int colg = (xk / per_col) * 8 + (blockIdx.x & 7);
+  const int rem = xk % per_col;
+  const int mt0 = (rem % wa.n_rowg) * MTW, slice = rem / wa.n_rowg;
+  if (colg >= wa.n_colg) return;
+  const int kb = slice * wa.slice_kt, ke = min(KT, kb + wa.slice_kt);
+  const int pair = colg * WIDE_WAVES + wave;
+  const int t0 = EPI == EPI_SWIGLU ? pair : 2 * pair, t1 = EPI == EPI_SWIGLU ? pair : 2 * pair + 1;
+  const u32x4* w0 = (const u32x4*)g.W0 + (size_t)(t0 < ntiles ? t0 : 0) * KT * 64 + lane;
+  const u32x4* w1 = (const u32x4*)g.W1 + (size_t)(t1 < ntiles ? t1 : 0) * KT * 64 + lane;
+  constexpr int U = 4;
+  u32x4 b0[U], b1[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u)
-    if (u < KT) { b0[u] = w0[(size_t)u * 64]; b1[u] = w1[(size_t)u * 64]; }
-  const float* A = (const float*)g.A;
-  constexpr int SU = 8;                                   // staging loads in flight per thread (x 32 bytes)
-  for (int i0 = tid; i0 < MTW * KT * 64; i0 += SU * WIDE_WAVES * 64) {
-    u32x4 x0[SU], x1[SU];
-#pragma unroll
-    for (int u = 0; u < SU; ++u) {
-      const int i = i0 + u * WIDE_WAVES * 64;
-      const int l = i & 63, f = i >> 6;                   // f = mt * KT + kt
-      const int mt = f / KT, kt = f - mt * KT;
-      const int row = (mt0 + mt) * 16 + (l & 15);
-      x0[u] = u32x4{0u, 0u, 0u, 0u};
-      x1[u] = x0[u];
-      if (i < MTW * KT * 64 && row < g.M) {
-        const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + kt * 32 + (l >> 4) * 8);
-        x0[u] = ap[0];
-        x1[u] = ap[1];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < SU; ++u) {
-      const int i = i0 + u * WIDE_WAVES * 64;
-      if (i < MTW * KT * 64) {
-        const SplitA sp = split_bf16(x0[u], x1[u]);
-        afrag[((i >> 6) * 2) * 64 + (i & 63)] = __builtin_bit_cast(u32x4, sp.hi);
-        afrag[((i >> 6) * 2 + 1) * 64 + (i & 63)] = __builtin_bit_cast(u32x4, sp.lo);
-      }
-    }
+  for (int u = 0; u < U; ++u) {
+    b0[u] = u32x4{0u, 0u, 0u, 0u};
+    b1[u] = b0[u];
+    if (kb + u < ke) { b0[u] = w0[(size_t)(kb + u) * 64]; b1[u] = w1[(size_t)(kb + u) * 64]; }
   }
-  __syncthreads();
+  const float* A = (const float*)g.A;
   f32x4 acc[MTW][2];
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt) { acc[mt][0] = f32x4{0, 0, 0, 0}; acc[mt][1] = f32x4{0, 0, 0, 0}; }
-  for (int kt0 = 0; kt0 < KT; kt0 += U) {
+  int cbase = kb;
+  for (int kt0 = kb; kt0 < ke; kt0 += U) {
+    if ((kt0 - kb) % KC == 0) {                           // stage the next chunk of the rows' activations
+      cbase = kt0;
+      const int n = min(KC, ke - kt0), total = MTW * n * 64;
+      if (kt0 != kb) __syncthreads();                     // every wave is done with the previous chunk
+      constexpr int SU = 8;                               // staging loads in flight per thread (x 32 bytes)
+      for (int i0 = tid; i0 < total; i0 += SU * WIDE_WAVES * 64) {
+        u32x4 x0[SU], x1[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+          const int i = i0 + u * WIDE_WAVES * 64;
+          const int l = i & 63, f = i >> 6;               // f = mt * n + k-tile in chunk
+          const int mt = f / n, kk = f - mt * n;
+          const int row = (mt0 + mt) * 16 + (l & 15);
+          x0[u] = u32x4{0u, 0u, 0u, 0u};
+          x1[u] = x0[u];
+          if (i < total && row < g.M) {
+            const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + (kt0 + kk) * 32 + (l >> 4) * 8);
+            x0[u] = ap[0];
+            x1[u] = ap[1];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+          const int i = i0 + u * WIDE_WAVES * 64;
+          if (i < total) {
+            const int l = i & 63, f = i >> 6;
+            const int mt = f / n, kk = f - mt * n;
+            const SplitA sp = split_bf16(x0[u], x1[u]);
+            afrag[((mt * KC + kk) * 2) * 64 + l] = __builtin_bit_cast(u32x4, sp.hi);
+            afrag[((mt * KC + kk) * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, sp.lo);
+          }
+        }
+      }
+      __syncthreads();
+    }
     u32x4 c0[U], c1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) { c0[u] = b0[u]; c1[u] = b1[u]; }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (kt0 + U + u < KT) {
+      if (kt0 + U + u < ke) {
         b0[u] = w0[(size_t)(kt0 + U + u) * 64];
         b1[u] = w1[(size_t)(kt0 + U + u) * 64];
       }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (kt0 + u < KT) {
+      if (kt0 + u < ke) {
         const bf16x8 bv0 = __builtin_bit_cast(bf16x8, c0[u]), bv1 = __builtin_bit_cast(bf16x8, c1[u]);
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) {
-          const int f = mt * KT + kt0 + u;
+          const int f = mt * KC + (kt0 + u - cbase);
           const bf16x8 hi = __builtin_bit_cast(bf16x8, afrag[(f * 2) * 64 + lane]);
           const bf16x8 lo = __builtin_bit_cast(bf16x8, afrag[(f * 2 + 1) * 64 + lane]);
           acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bv0, acc[mt][0], 0, 0, 0);
@@ -309,10 +331,8 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_swiglu_wide(GemmArgs g
       }
     }
   }
-  if (!live) return;
   // accumulator register r of lane l is element (row 4*(l/16)+r, col l%16) of the 16x16 tile
-  const int n = t * 16 + (lane & 15);
-  if (n >= g.N) return;
+  const int n0 = t0 * 16 + (lane & 15), n1 = t1 * 16 + (lane & 15);
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
@@ -320,8 +340,16 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_swiglu_wide(GemmArgs g
       const int row = (mt0 + mt) * 16 + (lane >> 4) * 4 + r;
       if (row < g.M) {
         const float v0 = acc[mt][0][r], v1 = acc[mt][1][r];
-        const float sg = v0 / (1.0f + expf(-v0));
-        ((float*)g.act)[(size_t)row * g.N + n] = sg * v1;
+        if (EPI == EPI_SWIGLU) {
+          if (n0 < g.N) {
+            const float sg = v0 / (1.0f + expf(-v0));
+            ((float*)g.act)[(size_t)row * g.N + n0] = sg * v1;
+          }
+        } else {
+          float* o = g.out + (size_t)slice * g.out_split_stride + (size_t)row * g.ldo;
+          if (n0 < g.N) o[n0] = v0;
+          if (n1 < g.N) o[n1] = v1;
+        }
       }
     }
 }

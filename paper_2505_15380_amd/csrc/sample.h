@@ -57,7 +57,15 @@ __global__ void __launch_bounds__(BLOCK) k_add_norm(float* h, const float* part,
   float ss = 0.f;
   for (int i = threadIdx.x; i < d; i += BLOCK) {
     float v = hr[i];
-    for (int s = 0; s < n_part; ++s) v += part[(size_t)s * part_stride + (size_t)m * d + i];
+    const float* pp = part + (size_t)m * d + i;
+    for (int s0 = 0; s0 < n_part; s0 += 4) {              // four loads in flight; the sum stays in ascending split order
+      float x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) x[u] = s0 + u < n_part ? pp[(size_t)(s0 + u) * part_stride] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (s0 + u < n_part) v += x[u];
+    }
     hr[i] = v;
     ss = fmaf(v, v, ss);
   }

@@ -309,7 +309,9 @@ struct ssd_kv {
   u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
-  bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared gate/up kernel (SSD_GEMM=narrow: the generic one)
+  bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared GEMM kernel (SSD_GEMM=narrow: the generic one)
+  bool narrow_down = false;  // SSD_GEMM=narrow_down: only the down projection on the generic kernel
+  int wide_mtw = 0;          // SSD_WIDE_MTW=1..4: row tiles per workgroup of the LDS-shared kernel (0: chosen per launch)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
   // host
@@ -460,6 +462,9 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
     kv->attn_mfma = !(env && strcmp(env, "valu") == 0);
     env = getenv("SSD_GEMM");
     kv->gemm_wide = !(env && strcmp(env, "narrow") == 0);
+    kv->narrow_down = env && strcmp(env, "narrow_down") == 0;
+    env = getenv("SSD_WIDE_MTW");
+    kv->wide_mtw = env ? atoi(env) : 0;
   }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
@@ -516,6 +521,55 @@ static int launch_gemm(const ssd_model* m, GemmArgs g, int items, hipStream_t st
     else hipLaunchKernelGGL((k_gemm_bf16<2, EPI, BF16>), dim3(items, cdiv(MT, 2)), dim3(BLOCK), 0, st, g);
   } else {
     hipLaunchKernelGGL((k_gemm_f32<EPI, F32>), dim3(items), dim3(BLOCK), 0, st, g);
+  }
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+// Launch shape of k_gemm_wide (see gemm.h) for M rows: fewest row groups of at most WIDE_MAX_MTW tiles, the largest
+// staged chunk that fits the LDS budget, and for k-split outputs one slice per chunk up to the partial buffer's capacity.
+struct WidePlan {
+  int mtw, grid;
+  size_t lds;
+  WideArgs wa;
+};
+static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices) {
+  WidePlan p;
+  const int MT = cdiv(M, 16), KT = K / 32;
+  int n_rowg = cdiv(MT, WIDE_MAX_MTW);
+  p.mtw = cdiv(MT, n_rowg);
+  if (mtw_forced >= 1 && mtw_forced <= WIDE_MAX_MTW) { p.mtw = mtw_forced; n_rowg = cdiv(MT, p.mtw); }
+  const int kc_max = (WIDE_LDS_BYTES / 2048 / p.mtw) & ~3;
+  const int n_pairs = partial ? cdiv(cdiv(N, 16), 2) : cdiv(N, 16);
+  p.wa.n_colg = cdiv(n_pairs, WIDE_WAVES);
+  p.wa.n_rowg = n_rowg;
+  p.wa.n_slices = partial ? std::min(max_slices, std::max(1, cdiv(KT, kc_max))) : 1;
+  p.wa.slice_kt = (cdiv(KT, p.wa.n_slices) + 3) & ~3;
+  p.wa.n_slices = cdiv(KT, p.wa.slice_kt);
+  p.wa.KC = std::min(kc_max, p.wa.slice_kt);
+  p.grid = 8 * cdiv(p.wa.n_colg, 8) * n_rowg * p.wa.n_slices;          // see the kernel's index map
+  p.lds = (size_t)p.mtw * p.wa.KC * 2048;
+  return p;
+}
+
+template <int EPI>
+static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
+  static const hipError_t lds_ok = [] {                   // more than 64 KB of dynamic LDS is opt-in, once per process
+    const void* fns[] = {(const void*)k_gemm_wide<1, EPI>, (const void*)k_gemm_wide<2, EPI>, (const void*)k_gemm_wide<3, EPI>,
+                         (const void*)k_gemm_wide<4, EPI>};
+    for (const void* f : fns) {
+      const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }();
+  if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
+  const dim3 grid(p.grid), block(WIDE_WAVES * 64);
+  switch (p.mtw) {
+    case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    default: hipLaunchKernelGGL((k_gemm_wide<4, EPI>), grid, block, p.lds, st, g, p.wa); break;
   }
   LAUNCH_CHECK();
   return SSD_OK;
@@ -667,10 +721,24 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   memset(&g0, 0, sizeof g0);
   g0.M = M; g0.kv = kv->v; g0.rows = rows; g0.nq = nq; g0.rope = m->rope;
   const size_t part_stride = (size_t)M * d;
-  // k-splits fill the machine when there is one group of row tiles; with more groups (see launch_gemm) the groups do
+  // k-splits fill the machine: about two workgroups per CU over (column pairs x row groups x splits), at least 8
+  // k-tiles per workgroup
   const int row_groups = m->c.dtype == SSD_DTYPE_BF16 && M > 32 ? cdiv(cdiv(M, 16), 2) : 1;
-  const int gs_o = std::max(1, pick_splits(nqd, cdiv(cdiv(d, 16), 2)) / row_groups);
-  const int gs_d = std::max(1, pick_splits(c.d_ffn, cdiv(cdiv(d, 16), 2)) / row_groups);
+  const int npairs_d = cdiv(cdiv(d, 16), 2);
+  auto splits_for = [&](int Kd) {
+    if (row_groups == 1) return pick_splits(Kd, npairs_d);
+    const int want = std::max(1, 2 * kv->cus / (npairs_d * row_groups));
+    return std::max(1, std::min(std::min(want, (Kd / 32) / 8), (int)MAX_SPLITS));
+  };
+  const int gs_o = splits_for(nqd);
+  const bool wide = m->c.dtype == SSD_DTYPE_BF16 && M > 32 && kv->gemm_wide;
+  // down projection: slices of the long k range per workgroup, if that still gives half the CUs a workgroup
+  // (measured: 18.7 vs 44.6 us per launch on the 1.5B shape at 72 rows, 168 workgroups; 18.7 vs 17.5 us on the 0.5B
+  // shape at 112 rows, where it has 80)
+  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, kv->wide_mtw, MAX_SPLITS);
+  const bool wide_down = wide && !kv->narrow_down &&
+                         2 * down_plan.wa.n_colg * down_plan.wa.n_rowg * down_plan.wa.n_slices >= kv->cus;
+  const int gs_d = wide_down ? down_plan.wa.n_slices : splits_for(c.d_ffn);
   int n_part = 0;
   int rc;
   for (int l = 0; l < c.n_layers; ++l) {
@@ -709,22 +777,9 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
     g.A = kv->xn; g.lda = d; g.W0 = L.wgate; g.W1 = L.wup; g.N = c.d_ffn; g.K = d; g.gs = 1; g.act = kv->act;
     {
       ProfScope ps(PROF_GATEUP, st);
-      // many rows: row tiles x 8 column-tile pairs per workgroup, activations shared through LDS (see gemm.h)
-      const int mtw = (size_t)2 * 16 * d * 4 <= (size_t)WIDE_LDS_BYTES ? 2 : 1;
-      if (m->c.dtype == SSD_DTYPE_BF16 && M > 32 && kv->gemm_wide && (size_t)mtw * 16 * d * 4 <= (size_t)WIDE_LDS_BYTES) {
-        const dim3 grid(8 * cdiv(cdiv(cdiv(c.d_ffn, 16), WIDE_WAVES), 8) * cdiv(cdiv(M, 16), mtw));   // see the kernel's index map
-        const size_t lds = (size_t)mtw * 16 * d * 4;
-        static const hipError_t lds_ok = [] {               // more than 64 KB of dynamic LDS is opt-in, once per process
-          hipError_t e = hipFuncSetAttribute((const void*)k_gemm_swiglu_wide<2>, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
-          if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)k_gemm_swiglu_wide<1>, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
-          return e;
-        }();
-        if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
-        if (mtw == 2) hipLaunchKernelGGL((k_gemm_swiglu_wide<2>), grid, dim3(WIDE_WAVES * 64), lds, st, g);
-        else hipLaunchKernelGGL((k_gemm_swiglu_wide<1>), grid, dim3(WIDE_WAVES * 64), lds, st, g);
-        LAUNCH_CHECK();
-        rc = SSD_OK;
+      if (wide) {                                          // many rows: activations shared through LDS (see gemm.h)
+        // two row tiles per workgroup: measured best on both shapes (more workgroups beat fewer weight re-reads)
+        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, kv->wide_mtw ? kv->wide_mtw : 2, 1), st);
       } else {
         rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st);
       }
@@ -734,7 +789,11 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
     g = g0;                                                // down projection -> k-split partials
     g.A = kv->act; g.lda = c.d_ffn; g.W0 = L.wdown; g.W1 = L.wdown; g.N = d; g.K = c.d_ffn; g.gs = gs_d;
     g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
-    { ProfScope ps(PROF_DOWN, st); rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st); }
+    {
+      ProfScope ps(PROF_DOWN, st);
+      if (wide_down) rc = launch_wide<EPI_PARTIAL>(g, down_plan, st);
+      else rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st);
+    }
     if (rc) return rc;
     n_part = gs_d;
   }
