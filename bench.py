@@ -151,6 +151,10 @@ def main():
         "config": {"workload": "half_b_k4: 0.5B-shaped bf16 target (24 layers, d=896, 14q/2kv x64, FFN 4864, V=6564), "
                                "4-layer draft, batch 1, prefix 1024, K=4, T=1", "beta": args.beta,
                    "weights": "independent N(0,0.02) target and draft"},
+        "accepted_draft_tokens_per_s": round(float(n_acc.sum()) / dt, 1),
+        # the same measured cycle time at other acceptance levels (tau = emitted tokens per cycle, 1 .. K+1): the
+        # acceptance of unrelated random draft/target weights says nothing about a trained pair
+        "tokens_per_s_if_tau": {str(t): round(t / (dt / steps), 1) for t in range(1, K + 2)},
         "mean_accepted_per_cycle": round(float(n_acc.mean()), 3),
         "emitted_per_cycle": round(emitted / steps, 3),
         "verify_us": round(verify_ms * 1e3, 1),
