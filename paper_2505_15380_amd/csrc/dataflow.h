@@ -41,7 +41,10 @@ typedef unsigned long long u64;
 constexpr int DF_B = 12;                  // tagged words a thread keeps in flight while it stages operands
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
 constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
-constexpr int DF_NPF = 4;                 // attention parts merged per flight
+#ifndef DF_NPF_N
+#define DF_NPF_N 4
+#endif
+constexpr int DF_NPF = DF_NPF_N;          // attention parts merged per flight
 constexpr long DF_SPIN_LIMIT = 1L << 18;
 // LDS words: staging | sums of squares | unit reduction buffers, overlaid by the attention buffers of the two units
 constexpr int DF_SQ_WORDS = 1024;
@@ -269,11 +272,6 @@ __device__ __forceinline__ void frag_from_lds(const uint32_t* p, u32x4& hi, u32x
              __builtin_amdgcn_perm(w1[1], w1[0], 0x07060302u), __builtin_amdgcn_perm(w1[3], w1[2], 0x07060302u)};
 }
 
-#ifdef SSD_TRACE_FINE
-#define DF_FINE(k) do { if (a.trace && threadIdx.x == 0 && ph.layer == 3) a.trace[(size_t)blockIdx.x * 512 + 256 + (((slot) - 2) % 10 / 2) * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define DF_FINE(k) do { } while (0)
-#endif
 #define DF_STAMP(slot) do { if (a.trace && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * 512 + (slot)] = wall_clock64(); } while (0)
 
 // Item of round 0 that `unit` takes when items start at unit `shift` and take every `stride`-th unit (stride 2: one
@@ -307,7 +305,6 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
   const int row = ut >> 4, col = ut & 15;
   const int rounds = (ph.items + NU - 1) / NU;
   for (int rd = 0; rd < rounds; ++rd) {
-    DF_FINE(0);
     const int item = rd * NU + uitem;
     int t0, t1, split, kb = 0, ke = 0;
     const bool valid = gemm_item<EPI>(ph, item, t0, t1, split);
@@ -350,7 +347,6 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
     }
     if (EPI == PE_RESID && live) { gn0 = ph.gain_next[n0]; gn1 = ph.gain_next[n1]; }
     if (rd == 0) DF_STAMP(slot);
-    DF_FINE(1);
     // ---- products
     f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
     const uint32_t* arow_p = As + arow * (ph.K + 4) + g * 8;
@@ -379,15 +375,10 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
       red[uw][0][obase + r * 16] = acc0[r];
       red[uw][1][obase + r * 16] = acc1[r];
     }
-#ifdef SSD_TRACE_FINE
-    if (acc0[0] == 123456.f) *sdead = 2;       // forces the products to be complete before the stamp
-#endif
-    DF_FINE(2);
     float sq = 0.f;
     if (ph.sq && row < M)
       for (int p = col; p < KT; p += 16) sq += sqs[row * KT + p];
     __syncthreads();
-    DF_FINE(4);
     float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
     float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
     if (ph.sq) {
@@ -446,7 +437,6 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
       }
     }
     if (rd == 0) DF_STAMP(slot + 1);
-    DF_FINE(5);
     __syncthreads();
   }
   return false;
@@ -828,15 +818,9 @@ __device__ __forceinline__ void df_load_kv(const DArgs& a, int layer, const DAtt
 
 __device__ __forceinline__ float df_exp2(float x) { return __builtin_amdgcn_exp2f(x); }     // x <= 0 here, or -inf
 
-#ifdef SSD_TRACE_FINE
-#define DF_AFINE(k) do { if (a.trace && threadIdx.x == 0 && layer == 3) a.trace[(size_t)blockIdx.x * 512 + 256 + 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define DF_AFINE(k) do { } while (0)
-#endif
 
 __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const DAttItem& it, uint32_t* lds,
                                               const int* srow, int* sdead, int slot) {
-  DF_AFINE(0);
   // The pool fragments are requested first: the queries of this layer are not there yet in any case.
   KVPre kvp;
   df_load_kv(a, layer, it, kvp);
@@ -903,7 +887,6 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
   __syncthreads();
   if (*sdead) return true;
   DF_STAMP(slot);
-  DF_AFINE(1);
   // ---- fragments of positions written by this launch come from the side buffer, at the pool's fragment slots
   if (wlive && kbase + 64 > it.len) {
 #pragma unroll
@@ -929,7 +912,6 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         }
       }
   }
-  DF_AFINE(2);
   float mrow[4], lrow[4];
   f32x4 oacc[4];
 #pragma unroll
@@ -949,10 +931,6 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
       z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[1]), k1, z, 0, 0, 0);
       s[t] = z;
     }
-#ifdef SSD_TRACE_FINE
-    if (s[0][0] == 123456.f && s[3][3] == 1.f) *sdead = 2;
-    DF_AFINE(6);
-#endif
     // element (reg r, tile t) = (query row r0 + 4g + r, key kbase + 16t + c16)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -977,10 +955,6 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
       lrow[r] = sum;
     }
     __builtin_amdgcn_wave_barrier();
-#ifdef SSD_TRACE_FINE
-    if (lrow[0] == 123456.f && lrow[3] == 1.f) *sdead = 2;
-    DF_AFINE(7);
-#endif
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       const u32x4* pp = (const u32x4*)(Pw + c16 * 64 + ks * 32 + g * 8);
@@ -1002,7 +976,6 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
     if (c16 == 0) { ML[(uw * 16 + row) * 2] = mrow[r]; ML[(uw * 16 + row) * 2 + 1] = lrow[r]; }
   }
   __syncthreads();
-  DF_AFINE(3);
   {
     const int row = ut >> 4, ch = ut & 15, d0 = ch * 4, qr = r0 + row;
     if (it.valid && qr < RG) {
@@ -1074,10 +1047,8 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
     }
   }
   DF_STAMP(slot + 1);
-  DF_AFINE(4);
   if (bad) *sdead = 1;
   __syncthreads();
-  DF_AFINE(5);
   return *sdead != 0;
 }
 

@@ -191,11 +191,6 @@ struct GemmPhase {
   void* out;              // PE_QKV: q (split rows); PE_SWIGLU: act (split rows); PE_LOGITS: logits (fp32)
 };
 
-#ifdef SSD_TRACE_FINE
-#define FINE_STAMP(k) do { if (a.trace && threadIdx.x == 0 && ph.layer == 3) a.trace[(size_t)blockIdx.x * 512 + 256 + (EPI) * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define FINE_STAMP(k) do { } while (0)
-#endif
 
 struct WPre {             // weight fragments of a wave's first PF_K k-tiles of its first item in a phase
   u32x4 b0[PF_K], b1[PF_K];
@@ -285,7 +280,6 @@ __device__ __forceinline__ void gemm_phase(const PArgs& a, const GemmPhase& ph, 
     const bool live = valid && row < M;
     const int n0 = t0 * 16 + col, n1 = t1 * 16 + col;
     f32x4 acc0 = f32x4{0, 0, 0, 0}, acc1 = f32x4{0, 0, 0, 0};
-    FINE_STAMP(0);
     // operand fragments of the first PF_K k-tiles, all in flight at once
     u32x4 xh[PF_K], xl[PF_K];
 #pragma unroll
@@ -339,17 +333,12 @@ __device__ __forceinline__ void gemm_phase(const PArgs& a, const GemmPhase& ph, 
       }
     }
     const int obase = (g * 4) * 16 + (lane & 15);
-#ifdef SSD_TRACE_FINE
-    if (acc0[0] == 123456.f) return;       // forces the products to be complete before the stamp
-#endif
-    FINE_STAMP(1);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       red[uw][0][obase + r * 16] = acc0[r];
       red[uw][1][obase + r * 16] = acc1[r];
     }
     __syncthreads();
-    FINE_STAMP(2);
     float v0 = (red[0][0][ut] + red[1][0][ut]) + (red[2][0][ut] + red[3][0][ut]);
     float v1 = (red[0][1][ut] + red[1][1][ut]) + (red[2][1][ut] + red[3][1][ut]);
     if (ph.sumsq) {
@@ -387,9 +376,7 @@ __device__ __forceinline__ void gemm_phase(const PArgs& a, const GemmPhase& ph, 
       __syncthreads();
     } else if (EPI == PE_SWIGLU) {
       if (live && n0 < ph.N) st_split((bf16_t*)ph.out, ph.N, row, n0, v0 / (1.0f + expf(-v0)) * v1);
-      FINE_STAMP(3);
       __syncthreads();
-      FINE_STAMP(4);
     } else if (EPI == PE_LOGITS) {
       if (live) {
         float* lg = (float*)ph.out;

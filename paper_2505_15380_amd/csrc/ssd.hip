@@ -651,11 +651,10 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   // output projection) get workgroups of their own after them, as far as the device has compute units.
   const int g_mlp = std::min(kv->persistent_wgs, cdiv(c.d_ffn / 16, 2));
   const int n_small = (c.n_q_heads + 2 * c.n_kv_heads) * 2 + B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) + npairs;
-  const char* ex = getenv("SSD_DF_EXTRA");
   // with compute units to spare every small-phase item gets a workgroup of its own (its waves then do not share their
   // SIMDs with a second item), else two items share one
-  const int small_stride = (!(ex && ex[0] == '1') && g_mlp + n_small <= kv->cus) ? 2 : 1;
-  const int G = (ex && ex[0] == '0') ? g_mlp : std::min(kv->cus, g_mlp + cdiv(small_stride * n_small, 2)), NU = 2 * G;
+  const int small_stride = g_mlp + n_small <= kv->cus ? 2 : 1;
+  const int G = std::min(kv->cus, g_mlp + cdiv(small_stride * n_small, 2)), NU = 2 * G;
   // limits: one round of attention (its units wait for each other's parts), query rows of an item, LDS staging capacity
   const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && small_stride * B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU &&
                     M * (c.d_model + 4) <= DF_AW && M * (nqd + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
@@ -676,7 +675,7 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.st_h = PR * c.d_model; a.st_sq = PR * (c.d_model / 32); a.st_q = PR * nqd; a.st_kvn = PR * 2 * c.n_kv_heads * 64;
   a.st_att_p = PR * c.n_q_heads * kv->NP * 96;
   a.part2 = kv->t_part2; a.st_part2 = (size_t)(c.d_ffn / 32) * PR * c.d_model;
-  a.NP = kv->NP; a.n_parts = n_parts; a.g_mlp = g_mlp; a.small_stride = (ex && ex[0] == '0') ? 1 : small_stride;
+  a.NP = kv->NP; a.n_parts = n_parts; a.g_mlp = g_mlp; a.small_stride = small_stride;
   a.bar = kv->bar;
   a.tag = ++kv->epoch;
   a.trace = kv->trace_on ? kv->trace : nullptr;
