@@ -18,6 +18,9 @@ MODEL_SHAPES = {
                       vocab=1000, n_embed=1100, dtype="bf16", qkv_bias=1, rope_base=1.0e6, rms_eps=1e-6),
     "mini_bf16_draft": dict(n_layers=1, d_model=256, n_q_heads=6, n_kv_heads=2, head_dim=64, d_ffn=768,
                             vocab=1000, n_embed=1100, dtype="bf16", qkv_bias=1, rope_base=1.0e6, rms_eps=1e-6),
+    # the same with head_dim 128 (the 1.5B shape's head size) for the kernels that are specialised on it
+    "mini128_bf16": dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ffn=768,
+                         vocab=1000, n_embed=1100, dtype="bf16", qkv_bias=1, rope_base=1.0e6, rms_eps=1e-6),
     # 0.5B-shaped target and its 4-layer draft
     "half_b": dict(n_layers=24, d_model=896, n_q_heads=14, n_kv_heads=2, head_dim=64, d_ffn=4864,
                    vocab=6564, n_embed=6564 + 4096, dtype="bf16", qkv_bias=1, rope_base=1.0e6, rms_eps=1e-6),

@@ -176,6 +176,38 @@ def test_batched_verify_beyond_one_row_tile_uses_matrix_core_attention():
     assert 0 < worst < 2e-2
 
 
+@pytest.mark.parametrize("shape_name,gemm,attn", [("mini_bf16", "", ""), ("mini128_bf16", "", ""), ("mini_bf16", "narrow", ""),
+                                                  ("mini128_bf16", "", "valu")])
+def test_batched_verify_many_rows_kernels(shape_name, gemm, attn, monkeypatch):
+    """Five ragged sequences x (K+1 = 8) rows = 40 rows: three row tiles, so the batched kernels run (matrix-core
+    attention for head_dim 64 and 128, the LDS-shared gate/up GEMM with a ragged last row group), and the generic
+    kernels they replace when switched off; all against the oracle."""
+    from tests.parity import Pair, verify_parity_step
+    for k, v in (("SSD_GEMM", gemm), ("SSD_ATTN", attn)):
+        if v:
+            monkeypatch.setenv(k, v)
+        else:
+            monkeypatch.delenv(k, raising=False)
+    shape = si.model_shape(shape_name)
+    B, K, steps = 5, 7, 2
+    lens = [40, 250, 300, 515, 64]
+    cap = max(lens) + steps * (K + 1) + 20
+    pair = Pair(shape_name, 777, cap, max_seqs=B, max_rows=K + 1, block_tokens=16)
+    for b in range(B):
+        pair.prefill(b, si.make_prefix(shape, 3, lens[b] - 3, 710 + b))
+    rng = np.random.default_rng(8)
+    cfg = dict(beta=0.2, temperature=1.0, top_k=0, greedy=False, seed=11)
+    worst = 0.0
+    for s in range(steps):
+        res = verify_parity_step(pair, cfg, K, s, rng, 2e-2, 2e-2, seqs=tuple(range(B)))
+        assert pair.kv.last_forward_path() == 1
+        worst = max(worst, max(r["dlogits"] for r in res))
+        for b in range(B):
+            pair.check_state(b, 2e-2, layers=[shape["n_layers"] - 1])
+        pair.check_free_stack()
+    assert 0 < worst < 2e-2
+
+
 def test_rollback_and_reverify():
     """After a verification that rejected drafts, positions below the new length are untouched, stale positions
     are overwritten by the next call, and an explicit rollback frees whole blocks in the documented order."""
