@@ -21,6 +21,7 @@ struct AttnArgs {
   float* ml_part;       // [M][nq][NC][2]
   int NC;               // chunk capacity of the partial buffers
   void* out;            // [M][nq*hd] (combine)
+  int nparts, tiles_per_wg;   // k_attn_part_mfma: grid.x = nparts x groups of tiles_per_wg row tiles (a multiple of 4)
 };
 
 template <int HD, typename KVT>
@@ -177,13 +178,16 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
   constexpr int KS = HD / 32, DT = HD / 16, NF = 4 * KS + 2 * DT;     // fragments of a chunk: 16 (HD 64) or 32 (HD 128)
   __shared__ __attribute__((aligned(16))) float Pw[4][16 * 64];
   __shared__ u32x4 KV[4][NF][64];                        // the part's fragments, [chunk][fragment][lane]
-  const int part = blockIdx.x, kvh = blockIdx.y, brel = blockIdx.z;
+  const int part = blockIdx.x % a.nparts, tgroup = blockIdx.x / a.nparts, kvh = blockIdx.y, brel = blockIdx.z;
   const int seq = a.rows.seq0 + brel;
   const int R = a.rows.R, nkv = a.kv.nkv, G = a.nq / nkv, RG = R * G;
   const int m_first = brel * R;
-  const int pos_max = a.rows.pos[m_first + R - 1];
+  const int ntiles = (RG + 15) >> 4;
+  const int rt_begin = tgroup * a.tiles_per_wg, rt_end = min(ntiles, rt_begin + a.tiles_per_wg);
+  // rows are in ascending position order: the last row of this workgroup's tiles sees the most keys
+  const int pos_max = a.rows.pos[m_first + (min(16 * rt_end, RG) - 1) / G];
   const int pbase = part * ATT_PART_KEYS;
-  if (pbase > pos_max) return;                           // no row of this sequence reaches the part
+  if (pbase > pos_max) return;                           // no row of these tiles reaches the part
   const int tid = threadIdx.x, lane = tid & 63, uw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c16 = lane & 15;
   const int nch = min(4, ((pos_max - pbase) >> 6) + 1);  // chunks of the part that some row reaches
@@ -203,7 +207,6 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
       for (int dt = 0; dt < DT; ++dt) KV[uw][4 * KS + ks * DT + dt][lane] = f.vf[ks][dt];
   }
   const float scale2 = a.scale * 1.4426950408889634f;
-  const int ntiles = (RG + 15) >> 4;
   float* P = Pw[uw];
   // Q fragments of the wave's first tile travel while the keys do
   auto load_q = [&](int rt, u32x4 (&x)[KS][2]) {
@@ -227,10 +230,12 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
   };
   u32x4 qraw[KS][2];
   int pos[4];
-  if (uw < ntiles) { load_q(uw, qraw); load_pos(uw, pos); }
+  if (rt_begin + uw < rt_end) { load_q(rt_begin + uw, qraw); load_pos(rt_begin + uw, pos); }
   __syncthreads();
-  for (int rt = uw; rt < ntiles; rt += 4) {
-    if (rt != uw) { load_q(rt, qraw); load_pos(rt, pos); }
+  for (int rt = rt_begin + uw; rt < rt_end; rt += 4) {
+    if (rt != rt_begin + uw) { load_q(rt, qraw); load_pos(rt, pos); }
+    // causal skip: positions ascend with the row, so a tile whose last row does not reach the part has nothing here
+    if (a.rows.pos[m_first + (min(16 * rt + 16, RG) - 1) / G] < pbase) continue;
     SplitA qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = split_bf16(qraw[ks][0], qraw[ks][1]);

@@ -283,7 +283,7 @@ extern "C" int ssd_model_destroy(ssd_model* m) {
 
 // ------------------------------------------------------------------------------------------------ kv
 constexpr int MAX_SPLITS = 16;   // capacity of the k-split partial buffer
-constexpr int MAX_ROWS = 128;
+constexpr int MAX_ROWS = 512;
 
 struct ssd_kv {
   const ssd_model* m;
@@ -587,7 +587,12 @@ static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, bool mfma
   if constexpr (std::is_same<DT, BF16>::value && (HD == 64 || HD == 128)) {
     if (mfma && a.kv.bt == 16) {                          // keys and values as matrix-core fragments, 256-key parts
       const int nparts = cdiv(nchunks * ATT_CHUNK, ATT_PART_KEYS);
-      hipLaunchKernelGGL((k_attn_part_mfma<HD>), dim3(nparts, nkv, B), dim3(BLOCK), 0, st, a);
+      // many query rows per sequence (prefill chunks): groups of row tiles get workgroups of their own
+      const int ntiles = cdiv(a.rows.R * (a.nq / nkv), 16);
+      const int groups = std::max(1, std::min(cdiv(ntiles, 4), cdiv(2048, nparts * nkv * B)));
+      a.nparts = nparts;
+      a.tiles_per_wg = (cdiv(ntiles, groups) + 3) & ~3;
+      hipLaunchKernelGGL((k_attn_part_mfma<HD>), dim3(nparts * cdiv(ntiles, a.tiles_per_wg), nkv, B), dim3(BLOCK), 0, st, a);
       LAUNCH_CHECK();
       hipLaunchKernelGGL((k_attn_combine_parts<HD, F32>), dim3(M * a.nq), dim3(WAVE), 0, st, a);
       LAUNCH_CHECK();

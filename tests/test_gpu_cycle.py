@@ -208,6 +208,26 @@ def test_batched_verify_many_rows_kernels(shape_name, gemm, attn, monkeypatch):
     assert 0 < worst < 2e-2
 
 
+@pytest.mark.parametrize("shape_name", ["mini_bf16", "mini128_bf16"])
+def test_prefill_in_large_chunks_then_verify(shape_name):
+    """Prefill of 700 tokens in chunks of 256 rows (many row tiles per sequence: groups of tiles per attention
+    workgroup, causal skipping of tiles that do not reach a part), cache contents against the oracle's, then two
+    verifications on top of it."""
+    from tests.parity import Pair, verify_parity_step
+    shape = si.model_shape(shape_name)
+    K = 4
+    pair = Pair(shape_name, 778, 800, max_seqs=1, max_rows=256, block_tokens=16)
+    pair.prefill(0, si.make_prefix(shape, 50, 650, 720))
+    assert pair.kv.last_forward_path() == 1
+    pair.check_state(0, 2e-2)
+    pair.check_free_stack()
+    rng = np.random.default_rng(9)
+    cfg = dict(beta=0.2, temperature=1.0, top_k=0, greedy=False, seed=12)
+    for s in range(2):
+        verify_parity_step(pair, cfg, K, s, rng, 2e-2, 2e-2)
+        pair.check_state(0, 2e-2, layers=[shape["n_layers"] - 1])
+
+
 def test_rollback_and_reverify():
     """After a verification that rejected drafts, positions below the new length are untouched, stale positions
     are overwritten by the next call, and an explicit rollback frees whole blocks in the documented order."""
