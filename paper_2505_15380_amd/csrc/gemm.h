@@ -229,7 +229,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
 // so they travel while the next chunk is staged.  Accumulation order of an element: k ascending, lo before hi.
 constexpr int WIDE_WAVES = 8;
 constexpr int WIDE_LDS_BYTES = 128 * 1024;
-constexpr int WIDE_MAX_MTW = 4;
+constexpr int WIDE_MAX_MTW = 8;
 
 struct WideArgs {
   int KC;            // k-tiles per staged chunk (multiple of 4, MTW * KC * 2048 <= WIDE_LDS_BYTES)

@@ -311,7 +311,7 @@ struct ssd_kv {
   bool dataflow = false;
   bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared GEMM kernel (SSD_GEMM=narrow: the generic one)
   bool narrow_down = false;  // SSD_GEMM=narrow_down: only the down projection on the generic kernel
-  int wide_mtw = 0;          // SSD_WIDE_MTW=1..4: row tiles per workgroup of the LDS-shared kernel (0: chosen per launch)
+  int wide_mtw = 0;          // SSD_WIDE_MTW=1..8: row tiles per workgroup of the LDS-shared kernel (0: chosen per launch)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
   // host
@@ -536,9 +536,12 @@ struct WidePlan {
 static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices) {
   WidePlan p;
   const int MT = cdiv(M, 16), KT = K / 32;
-  int n_rowg = cdiv(MT, WIDE_MAX_MTW);
+  int n_rowg = cdiv(MT, 4);
   p.mtw = cdiv(MT, n_rowg);
-  if (mtw_forced >= 1 && mtw_forced <= WIDE_MAX_MTW) { p.mtw = mtw_forced; n_rowg = cdiv(MT, p.mtw); }
+  if (mtw_forced >= 1 && mtw_forced <= WIDE_MAX_MTW) p.mtw = mtw_forced;
+  if (p.mtw == 5) p.mtw = 6;                              // instantiated: 1, 2, 3, 4, 6, 8
+  if (p.mtw == 7) p.mtw = 8;
+  n_rowg = cdiv(MT, p.mtw);
   const int kc_max = (WIDE_LDS_BYTES / 2048 / p.mtw) & ~3;
   const int n_pairs = partial ? cdiv(cdiv(N, 16), 2) : cdiv(N, 16);
   p.wa.n_colg = cdiv(n_pairs, WIDE_WAVES);
@@ -556,7 +559,7 @@ template <int EPI>
 static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
   static const hipError_t lds_ok = [] {                   // more than 64 KB of dynamic LDS is opt-in, once per process
     const void* fns[] = {(const void*)k_gemm_wide<1, EPI>, (const void*)k_gemm_wide<2, EPI>, (const void*)k_gemm_wide<3, EPI>,
-                         (const void*)k_gemm_wide<4, EPI>};
+                         (const void*)k_gemm_wide<4, EPI>, (const void*)k_gemm_wide<6, EPI>, (const void*)k_gemm_wide<8, EPI>};
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
       if (e != hipSuccess) return e;
@@ -569,7 +572,10 @@ static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
     case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI>), grid, block, p.lds, st, g, p.wa); break;
     case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI>), grid, block, p.lds, st, g, p.wa); break;
     case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    default: hipLaunchKernelGGL((k_gemm_wide<4, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    case 4: hipLaunchKernelGGL((k_gemm_wide<4, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    case 6: hipLaunchKernelGGL((k_gemm_wide<6, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    case 8: hipLaunchKernelGGL((k_gemm_wide<8, EPI>), grid, block, p.lds, st, g, p.wa); break;
+    default: return fail(SSD_EINVAL, "no wide GEMM for %d row tiles per workgroup", p.mtw);
   }
   LAUNCH_CHECK();
   return SSD_OK;
