@@ -871,7 +871,13 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
                 int next_stride, float* probs_out, size_t probs_seq_stride, bool probs_last_row_only,
                 float* logits_out, hipStream_t st) {
   const ssd_model_config& c = m->c;
-  const int pcap = kv->v.pcap, R = pcap + K, M = B * R, V = c.vocab;
+  // Rows per sequence that carry pending tokens: the cache's capacity, or less when the host knows that no sequence of
+  // the launch holds that many (a draft cache owes two tokens only right after a fully accepted cycle; at 16 sequences
+  // one row each instead of two keeps the draft steps on the persistent kernel).
+  int pcap = 1;
+  for (int s = 0; s < B; ++s) pcap = std::max(pcap, kv->npend_ub[s]);
+  pcap = std::min(pcap, kv->v.pcap);
+  const int R = pcap + K, M = B * R, V = c.vocab;
   int rc;
   if ((rc = kv_check_room(kv, 0, B, R, st))) return rc;
   if ((rc = forward_any(m, kv, 0, B, R, pcap, dev_x, K, true, st))) return rc;
