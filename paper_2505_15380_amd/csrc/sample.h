@@ -117,15 +117,15 @@ __device__ __forceinline__ float sblock_sum(float v, float* s16) {      // fixed
 
 // One workgroup per row.  Top-k keeps exactly k entries: everything above the k-th largest value, and of the
 // entries equal to it the ones with the lowest indices.
-__global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) {
+__device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row) {
   __shared__ float s16[16];
   __shared__ int i16[16];
   __shared__ int hist[256];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_krem, sh_idxmax;
   const int tid = threadIdx.x;
-  const float* x = w.logits + (size_t)blockIdx.x * w.ld;
-  float* p = w.probs + (size_t)blockIdx.x * w.probs_stride;
+  const float* x = w.logits + (size_t)row * w.ld;
+  float* p = w.probs + (size_t)row * w.probs_stride;
   const int V = w.V;
   // the row is read once into registers (all loads in flight together)
   float xv[SPER];
@@ -238,6 +238,8 @@ __global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) {
   }
 }
 
+__global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) { warp_softmax_row(w, blockIdx.x); }
+
 // ------------------------------------------------------------------------------ acceptance + resampling
 struct AcceptArgs {
   const float* pt;       // [B][K+1][V]
@@ -301,10 +303,10 @@ __device__ __forceinline__ unsigned long long sblock_excl_scan_u64(unsigned long
 //     summation tree): smallest j whose inclusive prefix exceeds floor(total * u).
 //  3. the last workgroup to finish commits every sequence in ascending order: len += pending + n, pending =
 //     emitted token, blocks past the new length go back to the free stack.
-__global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) {
+__device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
   __shared__ unsigned long long w16[16];
   __shared__ int sh_n, sh_tok, sh_last;
-  const int b = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int K = a.K, V = a.V;
   const float* pt = a.pt + (size_t)b * a.pt_seq_stride;
   const float* pd = a.pd + (size_t)b * K * V;
@@ -393,6 +395,18 @@ __global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) {
     kv_publish(a.kv, sq);
   }
   a.kv.ctl[2] = 0;
+}
+
+__global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) { accept_seq(a, blockIdx.x); }
+
+// One row per sequence (a draft step, an autoregressive step): the row's distribution and the token drawn from it in
+// one launch.  The probabilities go through memory between the two halves (the caller wants the row anyway, and the
+// halves assign elements to threads differently), so the arithmetic is that of the two kernels above, bit for bit.
+__global__ void __launch_bounds__(SBLOCK) k_warp_accept(WarpArgs w, AcceptArgs a) {
+  warp_softmax_row(w, blockIdx.x);
+  __threadfence_block();
+  __syncthreads();
+  accept_seq(a, blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------ small state kernels

@@ -893,23 +893,26 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
     w.ld = R * V;                       // one row per sequence
     w.probs = probs_out ? probs_out : kv->probs;
     w.probs_stride = probs_out ? probs_seq_stride : (size_t)V;
-    hipLaunchKernelGGL(k_warp_softmax, dim3(B), dim3(SBLOCK), 0, st, w);
     a.pt = w.probs; a.pt_seq_stride = w.probs_stride;
   } else {
     w.logits = kv->logits + (size_t)(pcap - 1) * V;   // row of the last pending token, then the K drafts
     // rows pcap-1 .. R-1 of every sequence are consecutive only when pcap == 1 (a target cache)
     w.probs = probs_out ? probs_out : kv->probs;
     w.probs_stride = V;
-    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(SBLOCK), 0, st, w);
     a.pt = w.probs; a.pt_seq_stride = (size_t)(K + 1) * V;
   }
-  LAUNCH_CHECK();
+  const bool one_row = probs_last_row_only || (K == 0 && pcap == 1);     // one row per sequence: fused with the sampling
+  if (!one_row) {
+    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(SBLOCK), 0, st, w);
+    LAUNCH_CHECK();
+  }
   a.pd = dev_pd; a.x = dev_x; a.uniforms = nullptr; a.seed = cfg->seed; a.step = step_ctr;
   a.B = B; a.K = K; a.V = V; a.beta = cfg->beta;
   a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
   a.kv = kv->v; a.seq0 = 0;
   a.slot_base = slot_base;
-  hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, st, a);
+  if (one_row) hipLaunchKernelGGL(k_warp_accept, dim3(B), dim3(SBLOCK), 0, st, w, a);
+  else hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, st, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
