@@ -227,7 +227,7 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
 // time (MTW * KC * 2 KB), and every wave runs its own pair over the whole k range of the workgroup against them,
 // so nothing is reduced across waves.  Weight fragments are prefetched U k-tiles ahead, across chunk boundaries,
 // so they travel while the next chunk is staged.  Accumulation order of an element: k ascending, lo before hi.
-constexpr int WIDE_WAVES = 8;
+constexpr int WIDE_WAVES = 8;              // waves per workgroup of the shape for about a hundred rows
 constexpr int WIDE_LDS_BYTES = 128 * 1024;
 constexpr int WIDE_MAX_MTW = 8;
 
@@ -237,8 +237,11 @@ struct WideArgs {
   int n_slices, n_rowg, n_colg;
 };
 
-template <int MTW, int EPI>
-__global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideArgs wa) {
+// W waves per workgroup, NPW column-tile pairs per wave.  (8, 1) is the shape described above; (4, 2) is for hundreds
+// of rows: a wave's activation fragment then feeds 8 MFMAs instead of 4 (half the LDS bandwidth per MFMA) and two
+// workgroups fit a CU, so one stages while the other contracts.
+template <int MTW, int EPI, int W, int NPW>
+__global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g, WideArgs wa) {
   extern __shared__ u32x4 afrag[];                        // [(mt * KC + kt in chunk) * 2 + {hi, lo}][lane]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int KT = g.K >> 5, KC = wa.KC;
@@ -252,22 +255,32 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideA
   const int mt0 = (rem % wa.n_rowg) * MTW, slice = rem / wa.n_rowg;
   if (colg >= wa.n_colg) return;
   const int kb = slice * wa.slice_kt, ke = min(KT, kb + wa.slice_kt);
-  const int pair = colg * WIDE_WAVES + wave;
-  const int t0 = EPI == EPI_SWIGLU ? pair : 2 * pair, t1 = EPI == EPI_SWIGLU ? pair : 2 * pair + 1;
-  const u32x4* w0 = (const u32x4*)g.W0 + (size_t)(t0 < ntiles ? t0 : 0) * KT * 64 + lane;
-  const u32x4* w1 = (const u32x4*)g.W1 + (size_t)(t1 < ntiles ? t1 : 0) * KT * 64 + lane;
-  constexpr int U = 4;
-  u32x4 b0[U], b1[U];
+  constexpr int NT = 2 * NPW;                             // column tiles of a wave: slot 2q from W0, slot 2q + 1 from W1
+  int tl[NT];
+  const u32x4* wp[NT];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    b0[u] = u32x4{0u, 0u, 0u, 0u};
-    b1[u] = b0[u];
-    if (kb + u < ke) { b0[u] = w0[(size_t)(kb + u) * 64]; b1[u] = w1[(size_t)(kb + u) * 64]; }
+  for (int q = 0; q < NPW; ++q) {
+    const int pair = (colg * W + wave) * NPW + q;
+    tl[2 * q] = EPI == EPI_SWIGLU ? pair : 2 * pair;
+    tl[2 * q + 1] = EPI == EPI_SWIGLU ? pair : 2 * pair + 1;
+    wp[2 * q] = (const u32x4*)g.W0 + (size_t)(tl[2 * q] < ntiles ? tl[2 * q] : 0) * KT * 64 + lane;
+    wp[2 * q + 1] = (const u32x4*)g.W1 + (size_t)(tl[2 * q + 1] < ntiles ? tl[2 * q + 1] : 0) * KT * 64 + lane;
   }
-  const float* A = (const float*)g.A;
-  f32x4 acc[MTW][2];
+  constexpr int U = NPW == 1 ? 4 : 2;                     // k-tiles of weights in flight per wave and tile (KC % 4 == 0)
+  u32x4 bw[NT][U];
 #pragma unroll
-  for (int mt = 0; mt < MTW; ++mt) { acc[mt][0] = f32x4{0, 0, 0, 0}; acc[mt][1] = f32x4{0, 0, 0, 0}; }
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      bw[t][u] = u32x4{0u, 0u, 0u, 0u};
+      if (kb + u < ke) bw[t][u] = wp[t][(size_t)(kb + u) * 64];
+    }
+  const float* A = (const float*)g.A;
+  f32x4 acc[MTW][NT];
+#pragma unroll
+  for (int mt = 0; mt < MTW; ++mt)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0, 0, 0, 0};
   int cbase = kb;
   for (int kt0 = kb; kt0 < ke; kt0 += U) {
     if ((kt0 - kb) % KC == 0) {                           // stage the next chunk of the rows' activations
@@ -275,11 +288,11 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideA
       const int n = min(KC, ke - kt0), total = MTW * n * 64;
       if (kt0 != kb) __syncthreads();                     // every wave is done with the previous chunk
       constexpr int SU = 8;                               // staging loads in flight per thread (x 32 bytes)
-      for (int i0 = tid; i0 < total; i0 += SU * WIDE_WAVES * 64) {
+      for (int i0 = tid; i0 < total; i0 += SU * W * 64) {
         u32x4 x0[SU], x1[SU];
 #pragma unroll
         for (int u = 0; u < SU; ++u) {
-          const int i = i0 + u * WIDE_WAVES * 64;
+          const int i = i0 + u * W * 64;
           const int l = i & 63, f = i >> 6;               // f = mt * n + k-tile in chunk
           const int mt = f / n, kk = f - mt * n;
           const int row = (mt0 + mt) * 16 + (l & 15);
@@ -293,7 +306,7 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideA
         }
 #pragma unroll
         for (int u = 0; u < SU; ++u) {
-          const int i = i0 + u * WIDE_WAVES * 64;
+          const int i = i0 + u * W * 64;
           if (i < total) {
             const int l = i & 63, f = i >> 6;
             const int mt = f / n, kk = f - mt * n;
@@ -305,41 +318,45 @@ __global__ void __launch_bounds__(WIDE_WAVES * 64) k_gemm_wide(GemmArgs g, WideA
       }
       __syncthreads();
     }
-    u32x4 c0[U], c1[U];
+    u32x4 cw[NT][U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) { c0[u] = b0[u]; c1[u] = b1[u]; }
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (kt0 + U + u < ke) {
-        b0[u] = w0[(size_t)(kt0 + U + u) * 64];
-        b1[u] = w1[(size_t)(kt0 + U + u) * 64];
-      }
+      for (int u = 0; u < U; ++u) cw[t][u] = bw[t][u];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (kt0 + U + u < ke) bw[t][u] = wp[t][(size_t)(kt0 + U + u) * 64];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (kt0 + u < ke) {
-        const bf16x8 bv0 = __builtin_bit_cast(bf16x8, c0[u]), bv1 = __builtin_bit_cast(bf16x8, c1[u]);
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt) {
           const int f = mt * KC + (kt0 + u - cbase);
           const bf16x8 hi = __builtin_bit_cast(bf16x8, afrag[(f * 2) * 64 + lane]);
           const bf16x8 lo = __builtin_bit_cast(bf16x8, afrag[(f * 2 + 1) * 64 + lane]);
-          acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bv0, acc[mt][0], 0, 0, 0);
-          acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, bv1, acc[mt][1], 0, 0, 0);
-          acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, bv0, acc[mt][0], 0, 0, 0);
-          acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, bv1, acc[mt][1], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, __builtin_bit_cast(bf16x8, cw[t][u]), acc[mt][t], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, __builtin_bit_cast(bf16x8, cw[t][u]), acc[mt][t], 0, 0, 0);
         }
       }
     }
   }
   // accumulator register r of lane l is element (row 4*(l/16)+r, col l%16) of the 16x16 tile
-  const int n0 = t0 * 16 + (lane & 15), n1 = t1 * 16 + (lane & 15);
+#pragma unroll
+  for (int q = 0; q < NPW; ++q)
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
+      const int n0 = tl[2 * q] * 16 + (lane & 15), n1 = tl[2 * q + 1] * 16 + (lane & 15);
       const int row = (mt0 + mt) * 16 + (lane >> 4) * 4 + r;
       if (row < g.M) {
-        const float v0 = acc[mt][0][r], v1 = acc[mt][1][r];
+        const float v0 = acc[mt][2 * q][r], v1 = acc[mt][2 * q + 1][r];
         if (EPI == EPI_SWIGLU) {
           if (n0 < g.N) {
             const float sg = v0 / (1.0f + expf(-v0));

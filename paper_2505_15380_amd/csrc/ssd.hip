@@ -526,27 +526,33 @@ static int launch_gemm(const ssd_model* m, GemmArgs g, int items, hipStream_t st
   return SSD_OK;
 }
 
-// Launch shape of k_gemm_wide (see gemm.h) for M rows: fewest row groups of at most WIDE_MAX_MTW tiles, the largest
-// staged chunk that fits the LDS budget, and for k-split outputs one slice per chunk up to the partial buffer's capacity.
+// Launch shape of k_gemm_wide (see gemm.h) for M rows: fewest row groups of at most 4 tiles, the largest staged chunk
+// that fits the LDS budget, and for k-split outputs one slice per chunk up to the partial buffer's capacity.  From 256
+// rows on: 4 waves x 2 pairs per wave, 4 row tiles and half the LDS budget, so that two workgroups share a CU.
 struct WidePlan {
-  int mtw, grid;
+  int mtw, grid, waves, npw;
   size_t lds;
   WideArgs wa;
 };
-static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices) {
+static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices, bool big) {
   WidePlan p;
   const int MT = cdiv(M, 16), KT = K / 32;
+  p.waves = big ? 4 : WIDE_WAVES;
+  p.npw = big ? 2 : 1;
   int n_rowg = cdiv(MT, 4);
   p.mtw = cdiv(MT, n_rowg);
   if (mtw_forced >= 1 && mtw_forced <= WIDE_MAX_MTW) p.mtw = mtw_forced;
+  if (big) p.mtw = 4;
   if (p.mtw == 5) p.mtw = 6;                              // instantiated: 1, 2, 3, 4, 6, 8
   if (p.mtw == 7) p.mtw = 8;
   n_rowg = cdiv(MT, p.mtw);
-  const int kc_max = (WIDE_LDS_BYTES / 2048 / p.mtw) & ~3;
+  const int lds_budget = big ? WIDE_LDS_BYTES / 2 : WIDE_LDS_BYTES;
+  const int kc_max = (lds_budget / 2048 / p.mtw) & ~3;
   const int n_pairs = partial ? cdiv(cdiv(N, 16), 2) : cdiv(N, 16);
-  p.wa.n_colg = cdiv(n_pairs, WIDE_WAVES);
+  p.wa.n_colg = cdiv(n_pairs, p.waves * p.npw);
   p.wa.n_rowg = n_rowg;
   p.wa.n_slices = partial ? std::min(max_slices, std::max(1, cdiv(KT, kc_max))) : 1;
+  if (big && partial) p.wa.n_slices = std::min(p.wa.n_slices, std::max(1, cdiv(256, p.wa.n_colg * n_rowg)));   // a workgroup per CU is enough
   p.wa.slice_kt = (cdiv(KT, p.wa.n_slices) + 3) & ~3;
   p.wa.n_slices = cdiv(KT, p.wa.slice_kt);
   p.wa.KC = std::min(kc_max, p.wa.slice_kt);
@@ -558,8 +564,10 @@ static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int
 template <int EPI>
 static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
   static const hipError_t lds_ok = [] {                   // more than 64 KB of dynamic LDS is opt-in, once per process
-    const void* fns[] = {(const void*)k_gemm_wide<1, EPI>, (const void*)k_gemm_wide<2, EPI>, (const void*)k_gemm_wide<3, EPI>,
-                         (const void*)k_gemm_wide<4, EPI>, (const void*)k_gemm_wide<6, EPI>, (const void*)k_gemm_wide<8, EPI>};
+    const void* fns[] = {(const void*)k_gemm_wide<1, EPI, 8, 1>, (const void*)k_gemm_wide<2, EPI, 8, 1>,
+                         (const void*)k_gemm_wide<3, EPI, 8, 1>, (const void*)k_gemm_wide<4, EPI, 8, 1>,
+                         (const void*)k_gemm_wide<6, EPI, 8, 1>, (const void*)k_gemm_wide<8, EPI, 8, 1>,
+                         (const void*)k_gemm_wide<4, EPI, 4, 2>};
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
       if (e != hipSuccess) return e;
@@ -567,15 +575,19 @@ static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
     return hipSuccess;
   }();
   if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
-  const dim3 grid(p.grid), block(WIDE_WAVES * 64);
-  switch (p.mtw) {
-    case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    case 4: hipLaunchKernelGGL((k_gemm_wide<4, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    case 6: hipLaunchKernelGGL((k_gemm_wide<6, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    case 8: hipLaunchKernelGGL((k_gemm_wide<8, EPI>), grid, block, p.lds, st, g, p.wa); break;
-    default: return fail(SSD_EINVAL, "no wide GEMM for %d row tiles per workgroup", p.mtw);
+  const dim3 grid(p.grid), block(p.waves * 64);
+  if (p.waves == 4) {
+    hipLaunchKernelGGL((k_gemm_wide<4, EPI, 4, 2>), grid, block, p.lds, st, g, p.wa);
+  } else {
+    switch (p.mtw) {
+      case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      case 4: hipLaunchKernelGGL((k_gemm_wide<4, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      case 6: hipLaunchKernelGGL((k_gemm_wide<6, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      case 8: hipLaunchKernelGGL((k_gemm_wide<8, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+      default: return fail(SSD_EINVAL, "no wide GEMM for %d row tiles per workgroup", p.mtw);
+    }
   }
   LAUNCH_CHECK();
   return SSD_OK;
@@ -745,7 +757,8 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   // down projection: slices of the long k range per workgroup, if that still gives half the CUs a workgroup
   // (measured: 18.7 vs 44.6 us per launch on the 1.5B shape at 72 rows, 168 workgroups; 18.7 vs 17.5 us on the 0.5B
   // shape at 112 rows, where it has 80)
-  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, kv->wide_mtw, MAX_SPLITS);
+  const bool big = M >= 256 && !kv->wide_mtw;
+  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, kv->wide_mtw, MAX_SPLITS, big);
   const bool wide_down = wide && !kv->narrow_down &&
                          2 * down_plan.wa.n_colg * down_plan.wa.n_rowg * down_plan.wa.n_slices >= kv->cus;
   const int gs_d = wide_down ? down_plan.wa.n_slices : splits_for(c.d_ffn);
@@ -789,7 +802,7 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
       ProfScope ps(PROF_GATEUP, st);
       if (wide) {                                          // many rows: activations shared through LDS (see gemm.h)
         // two row tiles per workgroup: measured best on both shapes (more workgroups beat fewer weight re-reads)
-        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, kv->wide_mtw ? kv->wide_mtw : 2, 1), st);
+        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, kv->wide_mtw ? kv->wide_mtw : 2, 1, big), st);
       } else {
         rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st);
       }
