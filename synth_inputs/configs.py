@@ -47,6 +47,10 @@ WORKLOADS = {
     "half_b_batch16": dict(target="half_b", draft="half_b_draft", seeds=dict(target=200, draft=201, prefix=402, rng=1234),
                            batch=16, prefix_range=(256, 4096), K=6, temperature=1.0, top_k=0, steps=64,
                            block_tokens=16),
+    # beyond the benchmark plan's five: 64 sequences x 8 rows = 512 rows in one verification
+    "half_b_batch64": dict(target="half_b", draft="half_b_draft", seeds=dict(target=200, draft=201, prefix=602, rng=1234),
+                           batch=64, prefix_range=(256, 2048), K=7, temperature=1.0, top_k=0, steps=16,
+                           block_tokens=16),
     "one_half_b_batch8": dict(target="one_half_b", draft="one_half_b_draft",
                               seeds=dict(target=500, draft=501, prefix=502, rng=1234),
                               batch=8, prefix_range=(1024, 2048), K=8, temperature=0.8, top_k=0, steps=64,
