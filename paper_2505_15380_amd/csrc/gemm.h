@@ -293,8 +293,8 @@ __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g
 #pragma unroll
         for (int u = 0; u < SU; ++u) {
           const int i = i0 + u * W * 64;
-          const int l = i & 63, f = i >> 6;               // f = mt * n + k-tile in chunk
-          const int mt = f / n, kk = f - mt * n;
+          const int l = i & 63, f = i >> 6;               // f = k-tile in chunk * MTW + mt (division by a constant)
+          const int kk = f / MTW, mt = f - kk * MTW;
           const int row = (mt0 + mt) * 16 + (l & 15);
           x0[u] = u32x4{0u, 0u, 0u, 0u};
           x1[u] = x0[u];
@@ -309,7 +309,7 @@ __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g
           const int i = i0 + u * W * 64;
           if (i < total) {
             const int l = i & 63, f = i >> 6;
-            const int mt = f / n, kk = f - mt * n;
+            const int kk = f / MTW, mt = f - kk * MTW;
             const SplitA sp = split_bf16(x0[u], x1[u]);
             afrag[((mt * KC + kk) * 2) * 64 + l] = __builtin_bit_cast(u32x4, sp.hi);
             afrag[((mt * KC + kk) * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, sp.lo);
