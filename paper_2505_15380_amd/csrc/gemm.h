@@ -230,9 +230,10 @@ __global__ void __launch_bounds__(BLOCK) k_gemm_bf16(GemmArgs g) {
 constexpr int WIDE_WAVES = 8;              // waves per workgroup of the shape for about a hundred rows
 constexpr int WIDE_LDS_BYTES = 128 * 1024;
 constexpr int WIDE_MAX_MTW = 8;
+constexpr int WIDE_SG = 4;                 // activation fragments a thread stages per chunk
 
 struct WideArgs {
-  int KC;            // k-tiles per staged chunk (multiple of 4, MTW * KC * 2048 <= WIDE_LDS_BYTES)
+  int KC;            // k-tiles per staged chunk (multiple of 4, MTW * KC <= WIDE_SG * waves, two buffers of MTW * KC * 2 KB)
   int slice_kt;      // k-tiles per workgroup (multiple of 4; the whole k range for the SwiGLU epilogue)
   int n_slices, n_rowg, n_colg;
 };
@@ -242,7 +243,7 @@ struct WideArgs {
 // workgroups fit a CU, so one stages while the other contracts.
 template <int MTW, int EPI, int W, int NPW>
 __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g, WideArgs wa) {
-  extern __shared__ u32x4 afrag[];                        // [(mt * KC + kt in chunk) * 2 + {hi, lo}][lane]
+  extern __shared__ u32x4 afrag[];                        // two buffers of [(mt * KC + kt in chunk) * 2 + {hi, lo}][lane]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int KT = g.K >> 5, KC = wa.KC;
   // Workgroups are dealt to the 8 XCDs round-robin by their index; the row groups of one (column group, slice) take
@@ -266,7 +267,7 @@ __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g
     wp[2 * q] = (const u32x4*)g.W0 + (size_t)(tl[2 * q] < ntiles ? tl[2 * q] : 0) * KT * 64 + lane;
     wp[2 * q + 1] = (const u32x4*)g.W1 + (size_t)(tl[2 * q + 1] < ntiles ? tl[2 * q + 1] : 0) * KT * 64 + lane;
   }
-  constexpr int U = NPW == 1 ? 4 : 2;                     // k-tiles of weights in flight per wave and tile (KC % 4 == 0)
+  constexpr int U = 4;                                    // k-tiles of weights in flight per wave and tile (KC % 4 == 0)
   u32x4 bw[NT][U];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -281,67 +282,72 @@ __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g
   for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0, 0, 0, 0};
-  int cbase = kb;
-  for (int kt0 = kb; kt0 < ke; kt0 += U) {
-    if ((kt0 - kb) % KC == 0) {                           // stage the next chunk of the rows' activations
-      cbase = kt0;
-      const int n = min(KC, ke - kt0), total = MTW * n * 64;
-      if (kt0 != kb) __syncthreads();                     // every wave is done with the previous chunk
-      constexpr int SU = 8;                               // staging loads in flight per thread (x 32 bytes)
-      for (int i0 = tid; i0 < total; i0 += SU * W * 64) {
-        u32x4 x0[SU], x1[SU];
+  // The rows' activations go through LDS a chunk of KC k-tiles at a time, two buffers: the loads of chunk c + 1 are
+  // in flight (in registers) while chunk c is contracted, and are split and written to the other buffer afterwards.
+  // A thread holds WIDE_SG fragments (16 floats each: KC * MTW <= WIDE_SG * W); one barrier per chunk.
+  u32x4 x0[WIDE_SG], x1[WIDE_SG];
+  auto load_chunk = [&](int kt0) {
+    const int n = min(KC, ke - kt0), total = MTW * n * 64;
 #pragma unroll
-        for (int u = 0; u < SU; ++u) {
-          const int i = i0 + u * W * 64;
-          const int l = i & 63, f = i >> 6;               // f = k-tile in chunk * MTW + mt (division by a constant)
-          const int kk = f / MTW, mt = f - kk * MTW;
-          const int row = (mt0 + mt) * 16 + (l & 15);
-          x0[u] = u32x4{0u, 0u, 0u, 0u};
-          x1[u] = x0[u];
-          if (i < total && row < g.M) {
-            const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + (kt0 + kk) * 32 + (l >> 4) * 8);
-            x0[u] = ap[0];
-            x1[u] = ap[1];
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < SU; ++u) {
-          const int i = i0 + u * W * 64;
-          if (i < total) {
-            const int l = i & 63, f = i >> 6;
-            const int kk = f / MTW, mt = f - kk * MTW;
-            const SplitA sp = split_bf16(x0[u], x1[u]);
-            afrag[((mt * KC + kk) * 2) * 64 + l] = __builtin_bit_cast(u32x4, sp.hi);
-            afrag[((mt * KC + kk) * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, sp.lo);
-          }
-        }
+    for (int u = 0; u < WIDE_SG; ++u) {
+      const int i = tid + u * W * 64;
+      const int l = i & 63, f = i >> 6;                   // f = k-tile in chunk * MTW + mt (division by a constant)
+      const int kk = f / MTW, mt = f - kk * MTW;
+      const int row = (mt0 + mt) * 16 + (l & 15);
+      x0[u] = u32x4{0u, 0u, 0u, 0u};
+      x1[u] = x0[u];
+      if (i < total && row < g.M) {
+        const u32x4* ap = (const u32x4*)(A + (size_t)row * g.lda + (kt0 + kk) * 32 + (l >> 4) * 8);
+        x0[u] = ap[0];
+        x1[u] = ap[1];
       }
-      __syncthreads();
     }
-    u32x4 cw[NT][U];
+  };
+  auto store_chunk = [&](int kt0, u32x4* buf) {
+    const int n = min(KC, ke - kt0), total = MTW * n * 64;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int u = 0; u < WIDE_SG; ++u) {
+      const int i = tid + u * W * 64;
+      if (i < total) {
+        const int l = i & 63, f = i >> 6;
+        const int kk = f / MTW, mt = f - kk * MTW;
+        const SplitA sp = split_bf16(x0[u], x1[u]);
+        buf[((mt * KC + kk) * 2) * 64 + l] = __builtin_bit_cast(u32x4, sp.hi);
+        buf[((mt * KC + kk) * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, sp.lo);
+      }
+    }
+  };
+  const int buf_words = MTW * KC * 2 * 64;                // u32x4 elements of one buffer
+  load_chunk(kb);
+  int cidx = 0;
+  for (int c0 = kb; c0 < ke; c0 += KC, ++cidx) {
+    u32x4* buf = afrag + (cidx & 1) * buf_words;
+    store_chunk(c0, buf);
+    __syncthreads();
+    if (c0 + KC < ke) load_chunk(c0 + KC);
+    const int cend = min(ke, c0 + KC);
+    for (int kt0 = c0; kt0 < cend; kt0 += U) {
+      // slot u holds k-tile kt0 + u and is refilled with k-tile kt0 + U + u as soon as its MFMAs are issued: U - 1
+      // k-tiles of weights stay in flight behind the one being contracted
 #pragma unroll
-      for (int u = 0; u < U; ++u) cw[t][u] = bw[t][u];
+      for (int u = 0; u < U; ++u) {
+        if (kt0 + u < cend) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+          for (int mt = 0; mt < MTW; ++mt) {
+            const int f = mt * KC + (kt0 + u - c0);
+            const bf16x8 hi = __builtin_bit_cast(bf16x8, buf[(f * 2) * 64 + lane]);
+            const bf16x8 lo = __builtin_bit_cast(bf16x8, buf[(f * 2 + 1) * 64 + lane]);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (kt0 + U + u < ke) bw[t][u] = wp[t][(size_t)(kt0 + U + u) * 64];
+            for (int t = 0; t < NT; ++t)
+              acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, __builtin_bit_cast(bf16x8, bw[t][u]), acc[mt][t], 0, 0, 0);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (kt0 + u < ke) {
+            for (int t = 0; t < NT; ++t)
+              acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, __builtin_bit_cast(bf16x8, bw[t][u]), acc[mt][t], 0, 0, 0);
+          }
+        }
+        if (kt0 + U + u < ke) {
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) {
-          const int f = mt * KC + (kt0 + u - cbase);
-          const bf16x8 hi = __builtin_bit_cast(bf16x8, afrag[(f * 2) * 64 + lane]);
-          const bf16x8 lo = __builtin_bit_cast(bf16x8, afrag[(f * 2 + 1) * 64 + lane]);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, __builtin_bit_cast(bf16x8, cw[t][u]), acc[mt][t], 0, 0, 0);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, __builtin_bit_cast(bf16x8, cw[t][u]), acc[mt][t], 0, 0, 0);
+          for (int t = 0; t < NT; ++t) bw[t][u] = wp[t][(size_t)(kt0 + U + u) * 64];
         }
       }
     }

@@ -547,17 +547,18 @@ static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int
   if (p.mtw == 7) p.mtw = 8;
   n_rowg = cdiv(MT, p.mtw);
   const int lds_budget = big ? WIDE_LDS_BYTES / 2 : WIDE_LDS_BYTES;
-  const int kc_max = (lds_budget / 2048 / p.mtw) & ~3;
+  const int kc_slice = (lds_budget / 2048 / p.mtw) & ~3;                 // k-tiles per slice of a k-split output
+  const int kc_max = (WIDE_SG * p.waves / p.mtw) & ~3;                   // k-tiles per staged chunk (two buffers of it)
   const int n_pairs = partial ? cdiv(cdiv(N, 16), 2) : cdiv(N, 16);
   p.wa.n_colg = cdiv(n_pairs, p.waves * p.npw);
   p.wa.n_rowg = n_rowg;
-  p.wa.n_slices = partial ? std::min(max_slices, std::max(1, cdiv(KT, kc_max))) : 1;
+  p.wa.n_slices = partial ? std::min(max_slices, std::max(1, cdiv(KT, kc_slice))) : 1;
   if (big && partial) p.wa.n_slices = std::min(p.wa.n_slices, std::max(1, cdiv(256, p.wa.n_colg * n_rowg)));   // a workgroup per CU is enough
   p.wa.slice_kt = (cdiv(KT, p.wa.n_slices) + 3) & ~3;
   p.wa.n_slices = cdiv(KT, p.wa.slice_kt);
   p.wa.KC = std::min(kc_max, p.wa.slice_kt);
   p.grid = 8 * cdiv(p.wa.n_colg, 8) * n_rowg * p.wa.n_slices;          // see the kernel's index map
-  p.lds = (size_t)p.mtw * p.wa.KC * 2048;
+  p.lds = (size_t)2 * p.mtw * p.wa.KC * 2048;
   return p;
 }
 
