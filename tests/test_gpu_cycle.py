@@ -283,3 +283,5 @@ def test_errors_are_reported_not_faulted():
     with pytest.raises(ssd.SSDError):
         ssd.ssd_verify(pair.gmodel, pair.kv, 2, torch.zeros((2, 7), dtype=torch.int32, device="cuda"),
                        torch.full((2, 7, V), 1.0 / V, dtype=torch.float32, device="cuda"), 7, cfg, 0)          # n_seqs > max_seqs
+    with pytest.raises(ssd.SSDError):                           # more than 512 rows per forward
+        ssd.KVCache(pair.gmodel, 33, 16, 40, 16, 4, 1)
