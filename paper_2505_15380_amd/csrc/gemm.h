@@ -1,5 +1,5 @@
-// Skinny GEMMs of the decoder: Y[M,N] = X[M,Kd] . W[N,Kd]^T with M = rows of one forward (<= 128).
-// At these M the work is weight streaming: every weight byte is read once, coalesced, and the
+// Skinny GEMMs of the decoder: Y[M,N] = X[M,Kd] . W[N,Kd]^T with M = rows of one forward (<= 512).
+// Up to a few tens of rows the work is weight streaming: every weight byte is read once, coalesced, and the
 // contraction runs on MFMA 16x16x32 bf16 tiles (rows padded to 16; padded rows cost nothing that matters).
 //
 // Work decomposition, identical for both storage types:
