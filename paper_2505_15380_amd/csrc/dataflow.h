@@ -42,7 +42,7 @@ constexpr int DF_B = 12;                  // tagged words a thread keeps in flig
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
 constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
 #ifndef DF_NPF_N
-#define DF_NPF_N 4
+#define DF_NPF_N 5
 #endif
 constexpr int DF_NPF = DF_NPF_N;          // attention parts merged per flight
 constexpr long DF_SPIN_LIMIT = 1L << 18;
