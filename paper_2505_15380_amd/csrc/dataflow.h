@@ -38,7 +38,10 @@
 namespace ssd {
 
 typedef unsigned long long u64;
-constexpr int DF_B = 12;                  // tagged words a thread keeps in flight while it stages operands
+#ifndef DF_B_N
+#define DF_B_N 12
+#endif
+constexpr int DF_B = DF_B_N;              // tagged words a thread keeps in flight while it stages operands
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
 constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
 #ifndef DF_NPF_N
@@ -590,7 +593,10 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
 // Sum of the ffn/32 down-projection partials in ascending order, residual, and the operand / statistics of the next
 // RMSNorm.  Task = (row, 32 output columns); thread (column c, group g of 8) sums the partials of its group, the
 // groups meet in LDS in ascending order.
-constexpr int DF_RW = 20;                 // partials a thread keeps in flight
+#ifndef DF_RW_N
+#define DF_RW_N 20
+#endif
+constexpr int DF_RW = DF_RW_N;            // partials a thread keeps in flight
 __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const u64* part2, uint32_t tag2, const u64* h_in,
                                                 u64* h_out, u64* hg_out, u64* sq_out, const float* gain_next, int shift,
                                                 uint32_t* lds, int* sdead, int slot) {
