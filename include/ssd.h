@@ -179,7 +179,9 @@ int ssd_profile_end(double* total_ms, int* launches);
  * 0 none yet, 1 one launch per operator (fp32 storage, more than 16 rows, head_dim other than 64),
  * 2 one persistent kernel with grid barriers between phases, 3 one persistent kernel whose phases are ordered by
  * tagged data words (the default for bf16 storage and at most 16 rows; the environment variable
- * SSD_FORWARD=barrier, read at ssd_kv_create, selects 2 instead). */
+ * SSD_FORWARD=barrier, read at ssd_kv_create, selects 2 instead), 4 the same kernel with the attention of a short prefix
+ * (at most 1520 cached positions) done by one workgroup per row tile instead of 256-key parts (the default for caches
+ * created with pending_cap 2; SSD_ATTN_WHOLE=1 selects it for every cache, 0 for none). */
 int ssd_kv_last_forward_path(const ssd_kv* kv);
 
 /* Phase trace of the persistent forward kernels: with enable != 0 every later forward on `kv` records, per

@@ -1058,7 +1058,259 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
   return *sdead != 0;
 }
 
+// ------------------------------------------------------------------------------------------------ attention, short prefixes
+// Up to DF_WHOLE_CHUNKS chunks of 64 keys (the host decides from its bound of the cached lengths, the same for a
+// verification and an autoregressive step from one state): item = (sequence, kv head, row tile) on a workgroup of its
+// own, no parts.  Wave w walks chunks w, w + 8, w + 16 with a running (max, sum, weighted values) per row, the eight
+// waves meet once in LDS, and the result goes out as operand words: no partial leaves the workgroup, which takes the
+// parts' hand-over (store, find, merge) out of every layer.
+constexpr int DF_WHOLE_CHUNKS = 24;
+struct DAttWhole {
+  int valid, b, kvh, rt, seq, len, nact, off, pos_last, nch;
+};
+
+__device__ __forceinline__ DAttWhole df_att_whole_item(const DArgs& a, int item, int ntile, int* sblk) {
+  DAttWhole it;
+  it.valid = item < a.n_seqs * a.nkv * ntile;
+  it.b = 0; it.kvh = 0; it.rt = 0;
+  if (it.valid) {
+    it.rt = item % ntile;
+    const int t = item / ntile;
+    it.b = t % a.n_seqs;
+    it.kvh = t / a.n_seqs;
+  }
+  it.seq = a.rows.seq0 + it.b;
+  it.len = __builtin_amdgcn_readfirstlane(ld_state(a.kv.len + it.seq));
+  const int npend = a.pcap ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.n_pend + it.seq)) : 0;
+  it.off = a.pcap - npend;
+  it.nact = a.rows.R - it.off;
+  it.pos_last = it.len + it.nact - 1;
+  it.nch = min(DF_WHOLE_CHUNKS, it.pos_last / 64 + 1);
+  // block ids of the sequence's positions, once per launch (masked positions may read any block)
+  for (int i = threadIdx.x; i < DF_WHOLE_CHUNKS * 4; i += PBLOCK) {
+    const int bid = (it.valid && i < a.kv.mbps && i * 16 <= it.pos_last) ? ld_state(a.kv.table + it.seq * a.kv.mbps + i) : -1;
+    sblk[i] = bid < 0 ? 0 : bid;
+  }
+  return it;
+}
+
+__device__ __forceinline__ void df_load_kv_chunk(const DArgs& a, int layer, int kvh, int chunk, const int* sblk, int lane, KVPre& kv) {
+  const size_t plane = (size_t)a.kv.n_blocks * a.kv.nkv * 1024;
+  const bf16_t* kp = (const bf16_t*)a.kv.pool + (size_t)(2 * layer) * plane;
+  const bf16_t* vp = kp + plane;
+  const int g = lane >> 4, c16 = lane & 15;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int koff = ((sblk[chunk * 4 + t] * a.kv.nkv + kvh) * 16 + c16) * 64 + g * 8;
+    kv.kf[t][0] = *(const u32x4*)(kp + koff);
+    kv.kf[t][1] = *(const u32x4*)(kp + koff + 32);
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int vblk = sblk[chunk * 4 + 2 * ks + (g >> 1)];
+    const int voff = (vblk * a.kv.nkv + kvh) * 1024 + c16 * 16 + (g & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) kv.vf[ks][dt] = *(const u32x4*)(vp + voff + dt * 256);
+  }
+}
+
+__device__ __forceinline__ bool df_attn_whole(const DArgs& a, int layer, const DAttWhole& it, uint32_t* lds, const int* sblk,
+                                              const int* srow, int* sdead, int slot) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c16 = lane & 15;
+  // the first two chunks of the wave are requested before anything else: the queries are not there yet in any case
+  KVPre kvp[2];
+  const bool live0 = it.valid && wave < it.nch, live1 = it.valid && wave + 8 < it.nch, live2 = it.valid && wave + 16 < it.nch;
+  if (live0) df_load_kv_chunk(a, layer, it.kvh, wave, sblk, lane, kvp[0]);
+  if (live1) df_load_kv_chunk(a, layer, it.kvh, wave + 8, sblk, lane, kvp[1]);
+  uint32_t* Qs = lds;                                  // [16 rows][64] operand words
+  bf16_t* Kn = (bf16_t*)(lds + 1024);                  // [16][64] new keys
+  bf16_t* Vn = (bf16_t*)(lds + 1536);                  // [16][64] new values
+  float* Pw = (float*)(lds + 2048) + wave * 1024;      // [16][64] per wave
+  float* MO = (float*)(lds + 2048 + 8192);             // [8 waves][16][64]
+  float* ML = (float*)(lds + 2048 + 16384);            // [8 waves][16][2]
+  const int R = a.rows.R, G = a.nq / a.nkv, nqd = a.nq * 64, RG = R * G;
+  const int r0 = 16 * it.rt, nrt = min(16, RG - r0);
+  const u64* q = a.q + (size_t)layer * a.st_q;
+  const u64* kvn = a.kvn + (size_t)layer * a.st_kvn;
+  u64* attn = a.attn + (size_t)layer * a.st_q;
+  const int* rowpos = srow + it.b * R;
+  const float sc2 = a.scale * 1.44269504088896340736f;
+  int qpos[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int qr = r0 + 4 * g + r;
+    qpos[r] = qr < RG ? rowpos[qr / G] : -1;
+  }
+  bool bad = false;
+  // ---- one flight per thread: the queries of the tile's rows and this launch's keys / values of the kv head
+  if (it.valid) {
+    constexpr int NB = 6;                               // 6 x 512 threads >= 1024 + 2048 words
+    const int nQ = nrt * 64, total = nQ + it.nact * 128;
+    const uint32_t q_off = (uint32_t)(q - a.tw), n_off = (uint32_t)(kvn - a.tw);
+    uint32_t off[NB], out[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int idx = u * PBLOCK + tid;
+      off[u] = 0xFFFFFFFFu;
+      if (idx < nQ) {
+        const int r = r0 + (idx >> 6), dd = idx & 63, j = r / G, gq = r - j * G;
+        off[u] = q_off + (uint32_t)((it.b * R + j) * nqd + (it.kvh * G + gq) * 64 + dd);
+      } else if (idx < total) {
+        const int i2 = idx - nQ, jn = i2 >> 7, which = (i2 >> 6) & 1, dd = i2 & 63;
+        off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
+      }
+    }
+    bad = !poll_words<NB>(a.tw, off, a.tag, out, a.bar + 64, (DF_HINT_OWN & 2) ? q + (size_t)(it.b * R) * nqd + (it.kvh * G) * 64 : a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const int idx = u * PBLOCK + tid;
+      if (idx < nQ) Qs[idx] = out[u];
+      else if (idx < total) {
+        const int i2 = idx - nQ, jn = i2 >> 7, which = (i2 >> 6) & 1, dd = i2 & 63;
+        (which ? Vn : Kn)[jn * 64 + dd] = (bf16_t)out[u];
+      }
+    }
+    for (int idx = nQ + tid; idx < 1024; idx += PBLOCK) Qs[idx] = 0u;       // padding rows of the tile
+  }
+  if (bad) *sdead = 1;
+  __syncthreads();
+  if (*sdead) return true;
+  DF_STAMP(slot);
+  float mrow[4], lrow[4];
+  f32x4 oacc[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { mrow[r] = -INFINITY; lrow[r] = 0.f; oacc[r] = f32x4{0, 0, 0, 0}; }
+  if (live0) {
+    u32x4 qh[2], ql[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) frag_from_lds(Qs + c16 * 64 + ks * 32 + g * 8, qh[ks], ql[ks]);
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const bool livej = j == 0 ? live0 : (j == 1 ? live1 : live2);
+      if (livej) {
+        KVPre& kc = kvp[j & 1];
+        const int kbase = 64 * (wave + 8 * j);
+        // fragments of positions written by this launch come from the side buffer, at the pool's fragment slots
+        if (kbase + 64 > it.len) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int jn = kbase + 16 * t + c16 - it.len;
+            if ((unsigned)jn < (unsigned)it.nact) {
+              kc.kf[t][0] = *(const u32x4*)(Kn + jn * 64 + g * 8);
+              kc.kf[t][1] = *(const u32x4*)(Kn + jn * 64 + 32 + g * 8);
+            }
+          }
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+              const int dim = 16 * dt + c16;
+#pragma unroll
+              for (int w = 0; w < 4; ++w) {
+                uint32_t x = kc.vf[ks][dt][w];
+                const int j0 = kbase + 32 * ks + 8 * g + 2 * w - it.len, j1 = j0 + 1;
+                if ((unsigned)j0 < (unsigned)it.nact) x = (x & 0xFFFF0000u) | (uint32_t)Vn[j0 * 64 + dim];
+                if ((unsigned)j1 < (unsigned)it.nact) x = (x & 0x0000FFFFu) | ((uint32_t)Vn[j1 * 64 + dim] << 16);
+                kc.vf[ks][dt][w] = x;
+              }
+            }
+        }
+        f32x4 s[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const bf16x8 k0 = __builtin_bit_cast(bf16x8, kc.kf[t][0]), k1 = __builtin_bit_cast(bf16x8, kc.kf[t][1]);
+          f32x4 z = f32x4{0, 0, 0, 0};
+          z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ql[0]), k0, z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ql[1]), k1, z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[0]), k0, z, 0, 0, 0);
+          z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qh[1]), k1, z, 0, 0, 0);
+          s[t] = z;
+        }
+        // element (reg r, tile t) = (query row r0 + 4g + r, key kbase + 16t + c16)
+        float alpha[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int pos = qpos[r];
+          float mx = -INFINITY;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const bool ok = kbase + 16 * t + c16 <= pos;
+            s[t][r] = ok ? s[t][r] * sc2 : -INFINITY;
+            mx = fmaxf(mx, s[t][r]);
+          }
+          const float mnew = fmaxf(mrow[r], row16_max(mx));
+          alpha[r] = (mrow[r] == -INFINITY) ? 0.f : df_exp2(mrow[r] - mnew);
+          float sum = 0.f;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const float p = (s[t][r] == -INFINITY) ? 0.f : df_exp2(s[t][r] - mnew);
+            Pw[(4 * g + r) * 64 + 16 * t + c16] = p;
+            sum += p;
+          }
+          mrow[r] = mnew;
+          lrow[r] = fmaf(lrow[r], alpha[r], row16_sum(sum));
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) oacc[dt][r] *= alpha[r];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const u32x4* pp = (const u32x4*)(Pw + c16 * 64 + ks * 32 + g * 8);
+          const SplitA pf = split_bf16(pp[0], pp[1]);
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt) {
+            const bf16x8 vv = __builtin_bit_cast(bf16x8, kc.vf[ks][dt]);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.lo, vv, oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf.hi, vv, oacc[dt], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_wave_barrier();               // P is rewritten by the next chunk
+        if (j == 0 && live2) df_load_kv_chunk(a, layer, it.kvh, wave + 16, sblk, lane, kvp[0]);   // its fragments are free now
+      }
+    }
+  }
+  // ---- the eight waves meet (fixed order: wave 0 .. 7) and the tile's rows go out as operand words
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * g + r;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) MO[(wave * 16 + row) * 64 + 16 * dt + c16] = oacc[dt][r];
+    if (c16 == 0) { ML[(wave * 16 + row) * 2] = mrow[r]; ML[(wave * 16 + row) * 2 + 1] = lrow[r]; }
+  }
+  __syncthreads();
+  if (tid < 256) {
+    const int row = tid >> 4, ch = tid & 15, d0 = ch * 4, qr = r0 + row;
+    if (it.valid && qr < RG) {
+      const int j = qr / G, gq = qr - j * G, m = it.b * R + j, head = it.kvh * G + gq;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 8; ++w) mx = fmaxf(mx, ML[(w * 16 + row) * 2]);
+      float l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < 8; ++w) {
+        const float mw = ML[(w * 16 + row) * 2];
+        const float e = (mw == -INFINITY) ? 0.f : df_exp2(mw - mx);
+        l = fmaf(ML[(w * 16 + row) * 2 + 1], e, l);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = fmaf(MO[(w * 16 + row) * 64 + d0 + i], e, o[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+    }
+  }
+  DF_STAMP(slot + 1);
+  __syncthreads();
+  return false;
+}
+
 // ------------------------------------------------------------------------------------------------ the kernel
+// WHOLE: attention of short prefixes without parts (df_attn_whole); the host picks the instantiation per launch.
+template <bool WHOLE>
 __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[DF_LDS_WORDS];
   __shared__ int srow[3 * 16];
@@ -1069,7 +1321,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int NU = gridDim.x * 2;
   // items of every phase kind, and the unit that takes item 0 (the kinds with few items go to different workgroups)
   const int n_qkv = (a.nq + 2 * a.nkv) * 2, ntile = (a.rows.R * (a.nq / a.nkv) + 15) >> 4,
-            n_att = a.n_seqs * a.nkv * a.n_parts * ntile, n_o = np, n_gu = a.ffn >> 4,
+            n_att = a.n_seqs * a.nkv * (WHOLE ? 1 : a.n_parts) * ntile, n_o = np, n_gu = a.ffn >> 4,
             n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
   const int st = a.small_stride;
   const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + st * n_qkv) % NU, s_o = (s_att + st * n_att) % NU,
@@ -1130,7 +1382,11 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
 
   df_embed_phase(a);
   if (df_start_barrier(a, &sdead)) return;
-  const DAttItem ait = df_att_item(a, df_item_of_unit(unit, s_att, NU, st), ntile, wave_k & 3, threadIdx.x & 63);
+  __shared__ int sblk[DF_WHOLE_CHUNKS * 4];
+  DAttItem ait = DAttItem{};
+  DAttWhole aw = DAttWhole{};
+  if (WHOLE) aw = df_att_whole_item(a, df_item_of_unit(u0, s_att, NU, st), ntile, sblk);     // the item has the workgroup (stride 2)
+  else ait = df_att_item(a, df_item_of_unit(unit, s_att, NU, st), ntile, wave_k & 3, threadIdx.x & 63);
   if (threadIdx.x < a.rows.M) {                           // per-row constants of the launch: position, active, block of the new key
     const int m = threadIdx.x;
     const int pos = ld_state(a.rows.pos + m);
@@ -1147,7 +1403,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
       if (df_gemm_phase<PE_QKV>(a, cur, lds, srow, &sdead, s0)) return;
     }
     if (g_a) {
-      if (df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
+      if (WHOLE ? df_attn_whole(a, l, aw, lds, sblk, srow, &sdead, s0 + 2) : df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
     }
     if (g_o) {
       const DPhase cur = make_o(l);

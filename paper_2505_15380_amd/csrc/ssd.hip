@@ -309,11 +309,14 @@ struct ssd_kv {
   u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
   size_t t_words = 0;
   bool dataflow = false;
+  bool attn_whole = false;   // barrier-free kernel: attention of short prefixes without parts.  Default: caches with two
+                             // pending slots (draft caches: one-row steps gain 10 %); SSD_ATTN_WHOLE=0 never, 1 every cache
   bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared GEMM kernel (SSD_GEMM=narrow: the generic one)
   bool narrow_down = false;  // SSD_GEMM=narrow_down: only the down projection on the generic kernel
   int wide_mtw = 0;          // SSD_WIDE_MTW=1..8: row tiles per workgroup of the LDS-shared kernel (0: chosen per launch)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
-  int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel
+  int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel, 4 the same with attention without parts
+  bool last_whole = false;
   // host
   int32_t* mirror_host;
   std::vector<int> len_ub, npend_ub;
@@ -460,6 +463,8 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   {
     const char* env = getenv("SSD_ATTN");
     kv->attn_mfma = !(env && strcmp(env, "valu") == 0);
+    env = getenv("SSD_ATTN_WHOLE");
+    kv->attn_whole = env ? (env[0] == '1' || (env[0] == '2' && pending_cap == 2)) : (pending_cap == 2);
     env = getenv("SSD_GEMM");
     kv->gemm_wide = !(env && strcmp(env, "narrow") == 0);
     kv->narrow_down = env && strcmp(env, "narrow_down") == 0;
@@ -674,13 +679,19 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   // Workgroups [0, g_mlp) take the MLP items (two 16-column items each); the phases with few items (QKV, attention,
   // output projection) get workgroups of their own after them, as far as the device has compute units.
   const int g_mlp = std::min(kv->persistent_wgs, cdiv(c.d_ffn / 16, 2));
-  const int n_small = (c.n_q_heads + 2 * c.n_kv_heads) * 2 + B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) + npairs;
+  // short prefixes: attention without parts (decided from the host's bound of the cached lengths alone, so that every
+  // forward from one cache state takes the same path whatever its row count)
+  const int att_tiles = B * c.n_kv_heads * cdiv(rows.R * grp, 16);
+  const bool whole = kv->attn_whole && max_len + 16 <= DF_WHOLE_CHUNKS * 64 &&
+                     g_mlp + (c.n_q_heads + 2 * c.n_kv_heads) * 2 + att_tiles + npairs <= kv->cus;
+  const int n_att_items = whole ? att_tiles : att_tiles * n_parts;
+  const int n_small = (c.n_q_heads + 2 * c.n_kv_heads) * 2 + n_att_items + npairs;
   // with compute units to spare every small-phase item gets a workgroup of its own (its waves then do not share their
   // SIMDs with a second item), else two items share one
   const int small_stride = g_mlp + n_small <= kv->cus ? 2 : 1;
   const int G = std::min(kv->cus, g_mlp + cdiv(small_stride * n_small, 2)), NU = 2 * G;
   // limits: one round of attention (its units wait for each other's parts), query rows of an item, LDS staging capacity
-  const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && small_stride * B * c.n_kv_heads * n_parts * cdiv(rows.R * grp, 16) <= NU &&
+  const bool fits = M <= 16 && rows.R * grp <= DF_ATT_ROWS && small_stride * n_att_items <= NU &&
                     M * (c.d_model + 4) <= DF_AW && M * (nqd + 4) <= DF_AW && M * (c.d_model / 32) <= DF_SQ_WORDS &&
                     c.n_layers <= 128 && 2 + 10 * c.n_layers + 2 <= 512;
   if (!fits) return -1;
@@ -704,7 +715,9 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.tag = ++kv->epoch;
   a.trace = kv->trace_on ? kv->trace : nullptr;
   ProfScope ps(PROF_PERSISTENT, st);
-  hipLaunchKernelGGL(k_forward_dataflow, dim3(G), dim3(PBLOCK), 0, st, a);
+  kv->last_whole = whole;
+  if (whole) hipLaunchKernelGGL(k_forward_dataflow<true>, dim3(G), dim3(PBLOCK), 0, st, a);
+  else hipLaunchKernelGGL(k_forward_dataflow<false>, dim3(G), dim3(PBLOCK), 0, st, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -723,7 +736,7 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   if (kv->persistent_wgs > 0 && M <= kv->p_rows) {
     if (kv->dataflow) {
       const int rc = forward_dataflow(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
-      if (rc >= 0) { kv->last_path = 3; return rc; }
+      if (rc >= 0) { kv->last_path = kv->last_whole ? 4 : 3; return rc; }
     }
     kv->last_path = 2;
     return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);

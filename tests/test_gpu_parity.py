@@ -130,6 +130,17 @@ def test_mini_bf16_long_prefix_parts_and_boundaries(n_prefix, K):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("n_prefix,K", [(40, 4), (250, 4), (254, 12), (700, 7), (1290, 4), (1500, 3)])
+def test_mini_bf16_attention_without_parts(n_prefix, K, monkeypatch):
+    """The barrier-free kernel's attention of short prefixes (one workgroup per row tile walks every chunk): one, two
+    and three rounds of chunks per wave, new positions crossing a chunk boundary, the longest prefix the mode takes."""
+    from tests.parity import run_verify_parity
+    monkeypatch.setenv("SSD_ATTN_WHOLE", "1")
+    r = run_verify_parity("mini", steps=3, K=K, beta=0.3, atol_logits=2e-2, atol_probs=2e-2, n_prefix=n_prefix)
+    assert r["path"] == 4, "attention without parts did not run"
+
+
+@pytest.mark.gpu
 def test_barrier_and_barrier_free_kernels_agree(monkeypatch):
     """Same model, prefix and drafts through both persistent kernels: logits agree to rounding (they share the
     arithmetic definitions but not every summation order), decisions given equal probabilities are covered above."""
@@ -142,7 +153,8 @@ def test_barrier_and_barrier_free_kernels_agree(monkeypatch):
     toks = si.make_prefix(shape, 0, 300, wl["seeds"]["prefix"])
     K, V = 4, shape["vocab"]
     outs = []
-    for mode, want in (("barrier", 2), ("", 3)):
+    for mode, whole, want in (("barrier", "0", 2), ("", "0", 3), ("", "1", 4)):
+        monkeypatch.setenv("SSD_ATTN_WHOLE", whole)
         if mode:
             monkeypatch.setenv("SSD_FORWARD", mode)
         else:
@@ -158,8 +170,8 @@ def test_barrier_and_barrier_free_kernels_agree(monkeypatch):
         torch.cuda.synchronize()
         assert sess.kv.last_forward_path() == want
         outs.append(logits.cpu().numpy())
-    assert np.isfinite(outs[0]).all() and np.isfinite(outs[1]).all()
-    assert np.abs(outs[0] - outs[1]).max() < 2e-3
+    assert all(np.isfinite(o).all() for o in outs)
+    assert np.abs(outs[0] - outs[1]).max() < 2e-3 and np.abs(outs[1] - outs[2]).max() < 2e-3
 
 
 @pytest.mark.gpu
