@@ -311,6 +311,14 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
   const float* pt = a.pt + (size_t)b * a.pt_seq_stride;
   const float* pd = a.pd + (size_t)b * K * V;
   const uint32_t seq = (uint32_t)(a.seq0 + b);
+  // a single sequence commits without waiting for anyone: its cache state is requested now (nothing but this kernel's
+  // own commit changes it), so that the commit at the end is stores only
+  const bool solo = a.kv.len != nullptr && a.B == 1;
+  int st_len = 0, st_npend = 0, st_owned = 0, st_top = 0, st_err = 0;
+  if (solo && tid == 0) {
+    st_len = a.kv.len[seq]; st_npend = a.kv.n_pend[seq]; st_owned = a.kv.owned[seq];
+    st_top = a.kv.ctl[0]; st_err = a.kv.ctl[1];
+  }
 
   if (tid < WAVE) {
     bool acc = false;
@@ -376,6 +384,27 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
     if (a.flags) a.flags[b] = fallback;
   }
   if (a.kv.len == nullptr) return;
+  if (solo) {                                              // kv_truncate + kv_publish on the values read at the start
+    if (tid == 0) {
+      const int new_len = st_len + st_npend + n;
+      const int keep = ceil_div(new_len, a.kv.bt);
+      int own = st_owned, top = st_top;
+      while (own > keep) {
+        --own;
+        a.kv.free_stack[top++] = a.kv.table[seq * a.kv.mbps + own];
+        a.kv.table[seq * a.kv.mbps + own] = -1;
+      }
+      a.kv.owned[seq] = own;
+      a.kv.ctl[0] = top;
+      a.kv.len[seq] = new_len;
+      a.kv.pend[seq * 2] = sh_tok;
+      a.kv.n_pend[seq] = 1;
+      a.kv.mirror[2 * seq] = new_len;
+      a.kv.mirror[2 * seq + 1] = 1;
+      a.kv.mirror[2 * a.kv.max_seqs] = st_err;
+    }
+    return;
+  }
   // ---- commit by the last workgroup to arrive
   if (tid == 0) {
     __threadfence();
