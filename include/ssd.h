@@ -188,7 +188,7 @@ int ssd_kv_last_forward_path(const ssd_kv* kv);
  * workgroup, 100 MHz wall-clock samples.  When `out` is non-NULL the samples of the last forward are copied out
  * first (synchronises `stream`): rows of 512 entries per workgroup, *n_wgs workgroups, cap >= 512 * workgroups.
  * Barrier kernel: out[wg*512 + 2*b] = arrival and [.. + 2*b+1] = release of grid barrier b for b < *n_samples / 2.
- * Barrier-free kernel: entry 0 = start; entries 2 + 10*layer + 2*k and + 1 = operands staged / outputs stored of phase
+ * Barrier-free kernel: entry 1 = entry of the workgroup, entry 0 = past the start barrier; entries 2 + 10*layer + 2*k and + 1 = operands staged / outputs stored of phase
  * k (0 QKV, 1 attention, 2 output projection, 3 MLP, 4 partial sum), 0 where the workgroup has no item. */
 int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
                        int* n_samples);

@@ -678,7 +678,7 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 }
 
 // ------------------------------------------------------------------------------------------------ phase 0
-// Rows, embedding, block reservation.  Item = row.
+// Rows and embedding.  Item = row.
 __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), usel = wave >> 2, ut = tid & 255;
   const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
@@ -686,14 +686,18 @@ __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
   for (int m = unit; m < M; m += NU) {
     const int brel = m / R, j = m - brel * R;
     const int seq = a.rows.seq0 + brel;
+    // every candidate is requested at once: which of them is the row's token follows from the pending count
     const int npend = a.pcap ? ld_state(a.kv.n_pend + seq) : 0;
-    const int off = a.pcap - npend;
     const int len = ld_state(a.kv.len + seq);
+    const int p0 = a.pcap ? ld_state(a.kv.pend + seq * 2) : 0;
+    const int p1 = a.pcap > 1 ? ld_state(a.kv.pend + seq * 2 + 1) : 0;
+    const int tx = j >= a.pcap ? ld_state(a.tokens + (size_t)brel * a.tok_stride + (j - a.pcap)) : 0;
+    const int off = a.pcap - npend;
     int tok, pos, active;
-    if (j < off) { tok = ld_state(a.kv.pend + seq * 2); pos = len; active = 0; }
+    if (j < off) { tok = p0; pos = len; active = 0; }
     else {
       pos = len + (j - off); active = 1;
-      tok = j < a.pcap ? ld_state(a.kv.pend + seq * 2 + (j - off)) : ld_state(a.tokens + (size_t)brel * a.tok_stride + (j - a.pcap));
+      tok = j < a.pcap ? ((j - off) ? p1 : p0) : tx;
     }
     tok = min(max(tok, 0), a.n_embed - 1);
     if (ut == 0) { st_ag(a.rows.pos + m, pos); st_ag(a.rows.active + m, active); }
@@ -710,13 +714,20 @@ __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
       if ((ut & 31) == 0) st_wordf(a.sq + (size_t)m * (d >> 5) + p, sq, a.tag);
     }
   }
-  if (blockIdx.x == 0 && tid == 0) {
+}
+
+// Block reservation for the rows of this launch, by one thread of the grid.  It runs first in the kernel: it is the
+// longest chain of dependent memory round trips before the start barrier, where every workgroup waits for it.
+__device__ __forceinline__ void df_reserve_blocks(const DArgs& a) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
     int top = ld_state(a.kv.ctl);
     for (int b = 0; b < a.n_seqs; ++b) {
       const int s = a.rows.seq0 + b;
-      const int o = a.pcap ? a.pcap - ld_state(a.kv.n_pend + s) : 0;
-      const int need = ceil_div(ld_state(a.kv.len + s) + a.rows.R - o, a.kv.bt);
+      const int np_s = a.pcap ? ld_state(a.kv.n_pend + s) : 0;       // three independent loads, one round trip
+      const int len_s = ld_state(a.kv.len + s);
       int own = ld_state(a.kv.owned + s);
+      const int o = a.pcap ? a.pcap - np_s : 0;
+      const int need = ceil_div(len_s + a.rows.R - o, a.kv.bt);
       while (own < need) {
         if (top <= 0 || own >= a.kv.mbps) { a.kv.ctl[1] = 1; break; }
         st_ag(a.kv.table + s * a.kv.mbps + own, ld_state(a.kv.free_stack + --top));
@@ -766,6 +777,10 @@ struct DAttItem {
   int koff[4], voff[2];
 };
 
+// Everything here is requested at once (one memory round trip, not six): the cached length and the pending count do
+// not change during the launch, and the block ids of positions below the cached length do not either, so this runs
+// before the start barrier.  Blocks that hold positions at or beyond the cached length may be reserved by phase 0:
+// df_att_item_fix re-reads those after the barrier.
 __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int ntile, int uw, int lane) {
   DAttItem it;
   it.valid = item < a.n_seqs * a.nkv * a.n_parts * ntile;
@@ -779,21 +794,28 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
     it.part = t / a.nkv;
   }
   it.seq = a.rows.seq0 + it.b;
-  it.len = __builtin_amdgcn_readfirstlane(ld_state(a.kv.len + it.seq));
-  const int npend = a.pcap ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.n_pend + it.seq)) : 0;
+  const int kbase = it.part * ATT_PART + uw * 64;
+  int len_v = ld_state(a.kv.len + it.seq);
+  int npend_v = a.pcap ? ld_state(a.kv.n_pend + it.seq) : 0;
+  int braw[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int bi = (kbase >> 4) + t;
+    braw[t] = (it.valid && bi < a.kv.mbps) ? ld_state(a.kv.table + it.seq * a.kv.mbps + bi) : -1;
+  }
+  it.len = __builtin_amdgcn_readfirstlane(len_v);
+  const int npend = __builtin_amdgcn_readfirstlane(npend_v);
   it.off = a.pcap - npend;
   it.nact = a.rows.R - it.off;
   it.pos_last = it.len + it.nact - 1;
   it.valid = it.valid && it.part * ATT_PART <= it.pos_last;
   it.nparts_b = it.pos_last / ATT_PART + 1;
-  const int kbase = it.part * ATT_PART + uw * 64;
   const int g = lane >> 4, c16 = lane & 15;
   int blk[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int bi = (kbase >> 4) + t;
-    const int b = (it.valid && bi < a.kv.mbps && bi * 16 <= it.pos_last)
-                      ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.table + it.seq * a.kv.mbps + bi)) : -1;
+    const int b = (it.valid && bi * 16 <= it.pos_last) ? __builtin_amdgcn_readfirstlane(braw[t]) : -1;
     blk[t] = b < 0 ? 0 : b;                                    // masked keys may read any block
     it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
   }
@@ -803,6 +825,27 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
     it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
   }
   return it;
+}
+
+// After the start barrier: the block ids of the wave's chunk that phase 0 may have reserved (blocks reaching to or
+// beyond the cached length), and the offsets that follow from them.
+__device__ __forceinline__ void df_att_item_fix(const DArgs& a, DAttItem& it, int uw, int lane) {
+  const int kbase = it.part * ATT_PART + uw * 64;
+  if (!it.valid || kbase + 64 <= it.len) return;               // every block of the chunk was cached before the launch
+  const int g = lane >> 4, c16 = lane & 15;
+  int blk[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int bi = (kbase >> 4) + t;
+    const int b = (bi < a.kv.mbps && bi * 16 <= it.pos_last) ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.table + it.seq * a.kv.mbps + bi)) : -1;
+    blk[t] = b < 0 ? 0 : b;
+    it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
+  }
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];
+    it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
+  }
 }
 
 // The 16 fragment loads of a wave's chunk from the pool.  Positions at or beyond the sequence's cached length hold
@@ -1080,18 +1123,30 @@ __device__ __forceinline__ DAttWhole df_att_whole_item(const DArgs& a, int item,
     it.kvh = t / a.n_seqs;
   }
   it.seq = a.rows.seq0 + it.b;
-  it.len = __builtin_amdgcn_readfirstlane(ld_state(a.kv.len + it.seq));
-  const int npend = a.pcap ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.n_pend + it.seq)) : 0;
+  // one round trip for all of it (see df_att_item): runs before the start barrier
+  const int len_v = ld_state(a.kv.len + it.seq);
+  const int npend_v = a.pcap ? ld_state(a.kv.n_pend + it.seq) : 0;
+  const int i = threadIdx.x;
+  int bid = -1;
+  if (i < DF_WHOLE_CHUNKS * 4 && it.valid && i < a.kv.mbps) bid = ld_state(a.kv.table + it.seq * a.kv.mbps + i);
+  it.len = __builtin_amdgcn_readfirstlane(len_v);
+  const int npend = __builtin_amdgcn_readfirstlane(npend_v);
   it.off = a.pcap - npend;
   it.nact = a.rows.R - it.off;
   it.pos_last = it.len + it.nact - 1;
   it.nch = min(DF_WHOLE_CHUNKS, it.pos_last / 64 + 1);
-  // block ids of the sequence's positions, once per launch (masked positions may read any block)
-  for (int i = threadIdx.x; i < DF_WHOLE_CHUNKS * 4; i += PBLOCK) {
-    const int bid = (it.valid && i < a.kv.mbps && i * 16 <= it.pos_last) ? ld_state(a.kv.table + it.seq * a.kv.mbps + i) : -1;
+  // block ids of the sequence's positions (masked positions may read any block)
+  if (i < DF_WHOLE_CHUNKS * 4) sblk[i] = (bid < 0 || i * 16 > it.pos_last) ? 0 : bid;
+  return it;
+}
+
+// After the start barrier: blocks that reach to or beyond the cached length may have been reserved by phase 0.
+__device__ __forceinline__ void df_att_whole_fix(const DArgs& a, const DAttWhole& it, int* sblk) {
+  const int i = threadIdx.x;
+  if (i < DF_WHOLE_CHUNKS * 4 && it.valid && i < a.kv.mbps && (i + 1) * 16 > it.len && i * 16 <= it.pos_last) {
+    const int bid = ld_state(a.kv.table + it.seq * a.kv.mbps + i);
     sblk[i] = bid < 0 ? 0 : bid;
   }
-  return it;
 }
 
 __device__ __forceinline__ void df_load_kv_chunk(const DArgs& a, int layer, int kvh, int chunk, const int* sblk, int lane, KVPre& kv) {
@@ -1380,20 +1435,33 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
              g_o = has(u0, s_o, n_o, st) || has(u1, s_o, n_o, st), g_g = (int)blockIdx.x < a.g_mlp,
              g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
 
-  df_embed_phase(a);
-  if (df_start_barrier(a, &sdead)) return;
+  DF_STAMP(1);
+  df_reserve_blocks(a);
+  // What the launch needs of the cache state is requested before phase 0 and the start barrier (none of it changes
+  // there, except block ids at or beyond the cached lengths, which are read again after the barrier): the waves'
+  // attention items, and per row its position and whether it is active.
   __shared__ int sblk[DF_WHOLE_CHUNKS * 4];
   DAttItem ait = DAttItem{};
   DAttWhole aw = DAttWhole{};
   if (WHOLE) aw = df_att_whole_item(a, df_item_of_unit(u0, s_att, NU, st), ntile, sblk);     // the item has the workgroup (stride 2)
   else ait = df_att_item(a, df_item_of_unit(unit, s_att, NU, st), ntile, wave_k & 3, threadIdx.x & 63);
-  if (threadIdx.x < a.rows.M) {                           // per-row constants of the launch: position, active, block of the new key
-    const int m = threadIdx.x;
-    const int pos = ld_state(a.rows.pos + m);
-    srow[m] = pos;
-    srow[16 + m] = ld_state(a.rows.active + m);
-    srow[32 + m] = (pos >> 4) < a.kv.mbps ? ld_state(a.kv.table + (a.rows.seq0 + m / a.rows.R) * a.kv.mbps + (pos >> 4)) : -1;
+  int row_pos = 0;
+  if (threadIdx.x < a.rows.M) {
+    const int m = threadIdx.x, brel = m / a.rows.R, j = m - brel * a.rows.R, seq = a.rows.seq0 + brel;
+    const int len = ld_state(a.kv.len + seq);
+    const int npend = a.pcap ? ld_state(a.kv.n_pend + seq) : 0;
+    const int off = a.pcap - npend;
+    row_pos = j < off ? len : len + (j - off);
+    srow[m] = row_pos;
+    srow[16 + m] = j < off ? 0 : 1;
   }
+  df_embed_phase(a);
+  if (df_start_barrier(a, &sdead)) return;
+  if (WHOLE) df_att_whole_fix(a, aw, sblk);
+  else df_att_item_fix(a, ait, wave_k & 3, threadIdx.x & 63);
+  if (threadIdx.x < a.rows.M)                             // block of the row's new key (reserved by phase 0 if it is a new block)
+    srow[32 + threadIdx.x] = (row_pos >> 4) < a.kv.mbps
+        ? ld_state(a.kv.table + (a.rows.seq0 + threadIdx.x / a.rows.R) * a.kv.mbps + (row_pos >> 4)) : -1;
   __syncthreads();
   DF_STAMP(0);
   for (int l = 0; l < L; ++l) {
