@@ -91,12 +91,13 @@ struct DArgs {
   u64* part2;             // [2][ffn/32][PR][d] fp32: down-projection partials of one 32-column slice of the SwiGLU output each,
                           // tagged with launch and layer (buffer = layer parity)
   size_t st_part2;
+  u64* rowblk;            // [16] per row: the pool block that takes the row's new key and value (-1: none), from the reservation
   float* logits;
   size_t st_h, st_sq, st_q, st_kvn, st_att_p;   // strides in words
   int NP, n_parts;
   int g_mlp;              // workgroups [0, g_mlp) take the MLP items; the phases with few items start on the workgroups after them
   int small_stride;       // 2: a small-phase item has a workgroup to itself; 1: two items per workgroup
-  uint32_t* bar;          // [0] arrivals, [32] flag, [64] error flag
+  uint32_t* bar;          // [64] error flag (sticky until the host reads it); [0], [32] belong to the kernel with grid barriers
   unsigned long long* trace;
 };
 
@@ -716,55 +717,61 @@ __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
   }
 }
 
-// Block reservation for the rows of this launch, by one thread of the grid.  It runs first in the kernel: it is the
-// longest chain of dependent memory round trips before the start barrier, where every workgroup waits for it.
+// Block reservation for the rows of this launch: lane b of the first wave of workgroup 0 takes sequence b (at most
+// 16 sequences).  Two memory round trips for all of them: the state words, then the ids (free-stack entries for new
+// blocks, table entries for blocks already owned).  Sequences take from the free stack in ascending order, top first,
+// as a serial walk over the sequences would.  Nothing waits for the table itself: the block that holds a row's new
+// key goes out as a tagged word per row (the workgroups with QKV items, whose epilogue appends the keys and values,
+// wait for it once), and attention never reads a position of this launch from the pool.  The launch therefore has no
+// grid barrier.
 __device__ __forceinline__ void df_reserve_blocks(const DArgs& a) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    int top = ld_state(a.kv.ctl);
-    for (int b = 0; b < a.n_seqs; ++b) {
-      const int s = a.rows.seq0 + b;
-      const int np_s = a.pcap ? ld_state(a.kv.n_pend + s) : 0;       // three independent loads, one round trip
-      const int len_s = ld_state(a.kv.len + s);
-      int own = ld_state(a.kv.owned + s);
-      const int o = a.pcap ? a.pcap - np_s : 0;
-      const int need = ceil_div(len_s + a.rows.R - o, a.kv.bt);
-      while (own < need) {
-        if (top <= 0 || own >= a.kv.mbps) { a.kv.ctl[1] = 1; break; }
-        st_ag(a.kv.table + s * a.kv.mbps + own, ld_state(a.kv.free_stack + --top));
-        ++own;
-      }
-      a.kv.owned[s] = own;
-    }
-    a.kv.ctl[0] = top;
+  if (blockIdx.x != 0 || threadIdx.x >= 64) return;
+  const int b = threadIdx.x, R = a.rows.R;
+  const bool on = b < a.n_seqs;
+  const int s = a.rows.seq0 + (on ? b : 0);
+  const int top = ld_state(a.kv.ctl);
+  const int np_s = a.pcap ? ld_state(a.kv.n_pend + s) : 0;
+  const int len_s = ld_state(a.kv.len + s);
+  const int own = ld_state(a.kv.owned + s);
+  const int off = a.pcap ? a.pcap - np_s : 0;
+  const int need = ceil_div(len_s + R - off, a.kv.bt);
+  const int want = on ? max(0, need - own) : 0, room = max(0, a.kv.mbps - own);
+  const int take = min(want, room);
+  int before = take;                                               // blocks that lower sequences take: exclusive prefix sum
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) {
+    const int v = __shfl_up(before, o, WAVE);
+    if (b >= o) before += v;
   }
-}
-
-// The one grid barrier of a launch: arrive on a counter; the last arrival clears it and publishes the launch
-// number on a separate line that the others poll.  Bounded.
-__device__ __forceinline__ bool df_start_barrier(const DArgs& a, int* sdead) {
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int dead = 0;
-    if (__hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, AG) == gridDim.x - 1) {
-      __hip_atomic_store(a.bar, 0u, __ATOMIC_RELAXED, AG);
-      __builtin_amdgcn_s_waitcnt(0);
-      __hip_atomic_store(a.bar + 32, a.tag, __ATOMIC_RELAXED, AG);
-    } else {
-      long spins = 0;
-      while ((int32_t)(__hip_atomic_load(a.bar + 32, __ATOMIC_RELAXED, AG) - a.tag) < 0) {
-        if (++spins > (1L << 21) || __hip_atomic_load(a.bar + 64, __ATOMIC_RELAXED, AG) != 0) {
-          __hip_atomic_store(a.bar + 64, 1u, __ATOMIC_RELAXED, AG);
-          dead = 1;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(1);
-      }
-    }
-    *sdead = dead;
+  const int total = __shfl(before, 15, WAVE);
+  before -= take;
+  const int got = max(0, min(take, top - before));
+  // ids of the (at most two) blocks that hold the positions of this launch's rows
+  const int bi0 = len_s >> 4;
+  int id[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int bi = bi0 + i;
+    id[i] = -1;
+    if (on && bi < own) id[i] = ld_state(a.kv.table + s * a.kv.mbps + bi);
+    else if (on && bi - own < got) id[i] = ld_state(a.kv.free_stack + (top - before - 1 - (bi - own)));
   }
-  __syncthreads();
-  return *sdead != 0;
+  if (on) {
+    for (int i = 0; i < got; ++i) {
+      const int bi = own + i;
+      const int v = bi == bi0 ? id[0] : bi == bi0 + 1 ? id[1] : ld_state(a.kv.free_stack + (top - before - 1 - i));
+      st_ag(a.kv.table + s * a.kv.mbps + bi, v);
+    }
+    a.kv.owned[s] = own + got;
+    if (got < want) a.kv.ctl[1] = 1;
+    for (int j = 0; j < R; ++j) {
+      const int pos = j < off ? len_s : len_s + (j - off);
+      const int bi = pos >> 4;
+      const int v = bi == bi0 ? id[0] : bi == bi0 + 1 ? id[1] : -1;
+      st_word(a.rowblk + b * R + j, (uint32_t)v, a.tag);
+    }
+  }
+  if (b == 0) a.kv.ctl[0] = max(0, top - total);
 }
 
 // ------------------------------------------------------------------------------------------------ attention
@@ -778,9 +785,10 @@ struct DAttItem {
 };
 
 // Everything here is requested at once (one memory round trip, not six): the cached length and the pending count do
-// not change during the launch, and the block ids of positions below the cached length do not either, so this runs
-// before the start barrier.  Blocks that hold positions at or beyond the cached length may be reserved by phase 0:
-// df_att_item_fix re-reads those after the barrier.
+// not change during the launch, and the block ids of positions below the cached length do not either.  A block all of
+// whose positions are at or beyond the cached length may be reserved concurrently by this launch: whatever id is read
+// for it is only checked to be inside the pool, since each of its positions is either a row of this launch (taken from
+// the tagged side buffer, never from the pool) or masked.
 __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int ntile, int uw, int lane) {
   DAttItem it;
   it.valid = item < a.n_seqs * a.nkv * a.n_parts * ntile;
@@ -795,13 +803,17 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
   }
   it.seq = a.rows.seq0 + it.b;
   const int kbase = it.part * ATT_PART + uw * 64;
-  int len_v = ld_state(a.kv.len + it.seq);
-  int npend_v = a.pcap ? ld_state(a.kv.n_pend + it.seq) : 0;
-  int braw[4];
+  // (only by the waves that have an item: a few hundred workgroups asking for the same words queue up at one channel)
+  int len_v = 0, npend_v = 0;
+  int braw[4] = {-1, -1, -1, -1};
+  if (it.valid) {
+    len_v = ld_state(a.kv.len + it.seq);
+    npend_v = a.pcap ? ld_state(a.kv.n_pend + it.seq) : 0;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int bi = (kbase >> 4) + t;
-    braw[t] = (it.valid && bi < a.kv.mbps) ? ld_state(a.kv.table + it.seq * a.kv.mbps + bi) : -1;
+    for (int t = 0; t < 4; ++t) {
+      const int bi = (kbase >> 4) + t;
+      if (bi < a.kv.mbps) braw[t] = ld_state(a.kv.table + it.seq * a.kv.mbps + bi);
+    }
   }
   it.len = __builtin_amdgcn_readfirstlane(len_v);
   const int npend = __builtin_amdgcn_readfirstlane(npend_v);
@@ -816,7 +828,7 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
   for (int t = 0; t < 4; ++t) {
     const int bi = (kbase >> 4) + t;
     const int b = (it.valid && bi * 16 <= it.pos_last) ? __builtin_amdgcn_readfirstlane(braw[t]) : -1;
-    blk[t] = b < 0 ? 0 : b;                                    // masked keys may read any block
+    blk[t] = (b < 0 || b >= a.kv.n_blocks) ? 0 : b;            // masked keys may read any block
     it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
   }
 #pragma unroll
@@ -825,27 +837,6 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
     it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
   }
   return it;
-}
-
-// After the start barrier: the block ids of the wave's chunk that phase 0 may have reserved (blocks reaching to or
-// beyond the cached length), and the offsets that follow from them.
-__device__ __forceinline__ void df_att_item_fix(const DArgs& a, DAttItem& it, int uw, int lane) {
-  const int kbase = it.part * ATT_PART + uw * 64;
-  if (!it.valid || kbase + 64 <= it.len) return;               // every block of the chunk was cached before the launch
-  const int g = lane >> 4, c16 = lane & 15;
-  int blk[4];
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int bi = (kbase >> 4) + t;
-    const int b = (bi < a.kv.mbps && bi * 16 <= it.pos_last) ? __builtin_amdgcn_readfirstlane(ld_state(a.kv.table + it.seq * a.kv.mbps + bi)) : -1;
-    blk[t] = b < 0 ? 0 : b;
-    it.koff[t] = ((blk[t] * a.nkv + it.kvh) * 16 + c16) * 64 + g * 8;
-  }
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int vblk = (g >> 1) ? blk[2 * ks + 1] : blk[2 * ks];
-    it.voff[ks] = (vblk * a.nkv + it.kvh) * 1024 + c16 * 16 + (g & 1) * 8;
-  }
 }
 
 // The 16 fragment loads of a wave's chunk from the pool.  Positions at or beyond the sequence's cached length hold
@@ -1123,9 +1114,9 @@ __device__ __forceinline__ DAttWhole df_att_whole_item(const DArgs& a, int item,
     it.kvh = t / a.n_seqs;
   }
   it.seq = a.rows.seq0 + it.b;
-  // one round trip for all of it (see df_att_item): runs before the start barrier
-  const int len_v = ld_state(a.kv.len + it.seq);
-  const int npend_v = a.pcap ? ld_state(a.kv.n_pend + it.seq) : 0;
+  // one round trip for all of it (see df_att_item)
+  const int len_v = it.valid ? ld_state(a.kv.len + it.seq) : 0;
+  const int npend_v = (it.valid && a.pcap) ? ld_state(a.kv.n_pend + it.seq) : 0;
   const int i = threadIdx.x;
   int bid = -1;
   if (i < DF_WHOLE_CHUNKS * 4 && it.valid && i < a.kv.mbps) bid = ld_state(a.kv.table + it.seq * a.kv.mbps + i);
@@ -1136,17 +1127,8 @@ __device__ __forceinline__ DAttWhole df_att_whole_item(const DArgs& a, int item,
   it.pos_last = it.len + it.nact - 1;
   it.nch = min(DF_WHOLE_CHUNKS, it.pos_last / 64 + 1);
   // block ids of the sequence's positions (masked positions may read any block)
-  if (i < DF_WHOLE_CHUNKS * 4) sblk[i] = (bid < 0 || i * 16 > it.pos_last) ? 0 : bid;
+  if (i < DF_WHOLE_CHUNKS * 4) sblk[i] = (bid < 0 || bid >= a.kv.n_blocks || i * 16 > it.pos_last) ? 0 : bid;
   return it;
-}
-
-// After the start barrier: blocks that reach to or beyond the cached length may have been reserved by phase 0.
-__device__ __forceinline__ void df_att_whole_fix(const DArgs& a, const DAttWhole& it, int* sblk) {
-  const int i = threadIdx.x;
-  if (i < DF_WHOLE_CHUNKS * 4 && it.valid && i < a.kv.mbps && (i + 1) * 16 > it.len && i * 16 <= it.pos_last) {
-    const int bid = ld_state(a.kv.table + it.seq * a.kv.mbps + i);
-    sblk[i] = bid < 0 ? 0 : bid;
-  }
 }
 
 __device__ __forceinline__ void df_load_kv_chunk(const DArgs& a, int layer, int kvh, int chunk, const int* sblk, int lane, KVPre& kv) {
@@ -1364,9 +1346,20 @@ __device__ __forceinline__ bool df_attn_whole(const DArgs& a, int layer, const D
 }
 
 // ------------------------------------------------------------------------------------------------ the kernel
+// The launch's arguments, read again from the kernel-argument segment through a pointer the compiler cannot see
+// through.  The arguments are some 130 dwords; held in scalar registers across the layer loop they do not fit, and
+// the compiler parks them in vector-register lanes (a readlane per use).  Every phase asks for the arguments anew,
+// so only what that phase uses is live, and the loads hit the scalar cache.
+__device__ __forceinline__ const DArgs& df_args() {
+  auto p = __builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(p));
+  return *(const DArgs*)p;
+}
+
 // WHOLE: attention of short prefixes without parts (df_attn_whole); the host picks the instantiation per launch.
 template <bool WHOLE>
-__global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
+__global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
+  const DArgs& a = df_args();
   __shared__ __attribute__((aligned(16))) uint32_t lds[DF_LDS_WORDS];
   __shared__ int srow[3 * 16];
   __shared__ uint32_t sact[16 * 36];
@@ -1381,7 +1374,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
   const int st = a.small_stride;
   const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + st * n_qkv) % NU, s_o = (s_att + st * n_att) % NU,
             s_red = (s_o + st * n_o) % NU;
-  auto make_qkv = [&](int l) {
+  auto make_qkv = [&](const DArgs& a, int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
@@ -1395,7 +1388,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     else if (l > 0) { x.hint = a.part2 + (size_t)((l - 1) & 1) * a.st_part2; x.hint_tag = df_tag2(a, l - 1); }
     return x;
   };
-  auto make_o = [&](int l) {
+  auto make_o = [&](const DArgs& a, int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l;
@@ -1409,7 +1402,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     else { x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = a.tag; }
     return x;
   };
-  auto make_swiglu = [&](int l) {
+  auto make_swiglu = [&](const DArgs& a, int l) {
     const PLayer Y = layer_ptrs(a, l);
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
@@ -1418,7 +1411,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     else { x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag; }
     return x;
   };
-  auto make_head = [&]() {
+  auto make_head = [&](const DArgs& a) {
     DPhase x = DPhase{};
     x.A = a.hg + (size_t)(2 * L) * a.st_h; x.sq = a.sq + (size_t)(2 * L) * a.st_sq;
     x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.stride = 1; x.logits = a.logits;
@@ -1437,52 +1430,60 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
 
   DF_STAMP(1);
   df_reserve_blocks(a);
-  // What the launch needs of the cache state is requested before phase 0 and the start barrier (none of it changes
-  // there, except block ids at or beyond the cached lengths, which are read again after the barrier): the waves'
-  // attention items, and per row its position and whether it is active.
+  // What the launch needs of the cache state (none of it changes during the launch): the waves' attention items, and
+  // per row its position and whether it is active.
   __shared__ int sblk[DF_WHOLE_CHUNKS * 4];
   DAttItem ait = DAttItem{};
   DAttWhole aw = DAttWhole{};
   if (WHOLE) aw = df_att_whole_item(a, df_item_of_unit(u0, s_att, NU, st), ntile, sblk);     // the item has the workgroup (stride 2)
   else ait = df_att_item(a, df_item_of_unit(unit, s_att, NU, st), ntile, wave_k & 3, threadIdx.x & 63);
-  int row_pos = 0;
-  if (threadIdx.x < a.rows.M) {
+  if ((g_q || g_a) && threadIdx.x < a.rows.M) {           // the QKV epilogue and the attention masks use them
     const int m = threadIdx.x, brel = m / a.rows.R, j = m - brel * a.rows.R, seq = a.rows.seq0 + brel;
     const int len = ld_state(a.kv.len + seq);
     const int npend = a.pcap ? ld_state(a.kv.n_pend + seq) : 0;
     const int off = a.pcap - npend;
-    row_pos = j < off ? len : len + (j - off);
-    srow[m] = row_pos;
+    srow[m] = j < off ? len : len + (j - off);
     srow[16 + m] = j < off ? 0 : 1;
   }
   df_embed_phase(a);
-  if (df_start_barrier(a, &sdead)) return;
-  if (WHOLE) df_att_whole_fix(a, aw, sblk);
-  else df_att_item_fix(a, ait, wave_k & 3, threadIdx.x & 63);
-  if (threadIdx.x < a.rows.M)                             // block of the row's new key (reserved by phase 0 if it is a new block)
-    srow[32 + threadIdx.x] = (row_pos >> 4) < a.kv.mbps
-        ? ld_state(a.kv.table + (a.rows.seq0 + threadIdx.x / a.rows.R) * a.kv.mbps + (row_pos >> 4)) : -1;
+  if (g_q && threadIdx.x < a.rows.M) {                    // the QKV epilogue appends keys and values: block of each row's position
+    u64 w = ld_word(a.rowblk + threadIdx.x);
+    for (long spins = 0; (uint32_t)(w >> 32) != a.tag; w = ld_word(a.rowblk + threadIdx.x)) {
+      if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(a.bar + 64, __ATOMIC_RELAXED, AG) != 0)) {
+        __hip_atomic_store(a.bar + 64, 1u, __ATOMIC_RELAXED, AG);
+        w = 0xFFFFFFFFull;                                 // no block: the row is not appended, every later wait sees the flag
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    srow[32 + threadIdx.x] = (int)(uint32_t)w;
+  }
   __syncthreads();
   DF_STAMP(0);
   for (int l = 0; l < L; ++l) {
     const int s0 = 2 + l * 10;
     if (g_q) {
-      const DPhase cur = make_qkv(l);
+      const DArgs& a = df_args();
+      const DPhase cur = make_qkv(a, l);
       if (df_gemm_phase<PE_QKV>(a, cur, lds, srow, &sdead, s0)) return;
     }
     if (g_a) {
+      const DArgs& a = df_args();
       if (WHOLE ? df_attn_whole(a, l, aw, lds, sblk, srow, &sdead, s0 + 2) : df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
     }
     if (g_o) {
-      const DPhase cur = make_o(l);
+      const DArgs& a = df_args();
+      const DPhase cur = make_o(a, l);
       if (df_gemm_phase<PE_RESID>(a, cur, lds, srow, &sdead, s0 + 4)) return;
     }
     if (g_g) {
-      const DPhase cur = make_swiglu(l);
+      const DArgs& a = df_args();
+      const DPhase cur = make_swiglu(a, l);
       u64* p2 = a.part2 + (size_t)(l & 1) * a.st_part2;
       if (df_mlp_phase(a, cur, layer_ptrs(a, l).wdown, p2, df_tag2(a, l), lds, sact, &sdead, s0 + 6)) return;
     }
     if (g_r) {
+      const DArgs& a = df_args();
       const size_t hi = (size_t)(2 * l + 1);
       const float* gain_next = l + 1 < L ? layer_ptrs(a, l + 1).ln1 : a.final_norm;
       if (df_reduce_phase(a, l, a.part2 + (size_t)(l & 1) * a.st_part2, df_tag2(a, l), a.h + hi * a.st_h, a.h + (hi + 1) * a.st_h,
@@ -1490,7 +1491,8 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs a) {
     }
   }
   if (a.with_head && g_l) {
-    const DPhase cur = make_head();
+    const DArgs& a = df_args();
+    const DPhase cur = make_head(a);
     df_gemm_phase<PE_LOGITS>(a, cur, lds, srow, &sdead, 2 + L * 10);
   }
 }

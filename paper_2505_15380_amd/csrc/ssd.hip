@@ -306,7 +306,7 @@ struct ssd_kv {
   int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
   int cus = 0;                     // compute units of the device
   // tagged workspace of the barrier-free forward (see dataflow.h); null when that kernel is not usable
-  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2;
+  u64 *t_base = nullptr, *t_h, *t_hg, *t_sq, *t_q, *t_kvn, *t_attn, *t_att_p, *t_part2, *t_rowblk;
   size_t t_words = 0;
   bool dataflow = false;
   bool attn_whole = false;   // barrier-free kernel: attention of short prefixes without parts.  Default: caches with two
@@ -369,13 +369,14 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   const size_t w_q = (size_t)L * TR * nqd, w_kvn = (size_t)L * TR * 2 * c.n_kv_heads * 64;
   const size_t w_attp = (size_t)L * TR * c.n_q_heads * NP * 96;
   const size_t w_part2 = (size_t)2 * (c.d_ffn / 32) * TR * c.d_model;
-  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_attp + w_part2;
+  const size_t t_words = w_h * 2 + w_sq + w_q * 2 + w_kvn + w_attp + w_part2 + 16;
   u64* t_base = cv.take<u64>(t_words);
   if (kv) {
     u64* t = t_base;
     kv->t_base = t_base; kv->t_words = t_words;
     kv->t_h = t; t += w_h; kv->t_hg = t; t += w_h; kv->t_sq = t; t += w_sq; kv->t_q = t; t += w_q; kv->t_attn = t; t += w_q;
-    kv->t_kvn = t; t += w_kvn; kv->t_att_p = t; t += w_attp; kv->t_part2 = t;
+    kv->t_kvn = t; t += w_kvn; kv->t_att_p = t; t += w_attp; kv->t_part2 = t; t += w_part2;
+    kv->t_rowblk = t;
 
     kv->trace = trace;
     kv->p_h = p_h; kv->p_hg = p_hg; kv->p_sumsq = p_sumsq; kv->p_q = p_q; kv->p_attn = p_attn; kv->p_act = p_act; kv->p_part = p_part; kv->p_att_o = p_att_o;
@@ -709,6 +710,7 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.att_p = kv->t_att_p; a.logits = kv->logits;
   a.st_h = PR * c.d_model; a.st_sq = PR * (c.d_model / 32); a.st_q = PR * nqd; a.st_kvn = PR * 2 * c.n_kv_heads * 64;
   a.st_att_p = PR * c.n_q_heads * kv->NP * 96;
+  a.rowblk = kv->t_rowblk;
   a.part2 = kv->t_part2; a.st_part2 = (size_t)(c.d_ffn / 32) * PR * c.d_model;
   a.NP = kv->NP; a.n_parts = n_parts; a.g_mlp = g_mlp; a.small_stride = small_stride;
   a.bar = kv->bar;
