@@ -823,7 +823,12 @@ __device__ __forceinline__ DAttItem df_att_item(const DArgs& a, int item, int nt
   it.valid = it.valid && it.part * ATT_PART <= it.pos_last;
   it.nparts_b = it.pos_last / ATT_PART + 1;
   const int g = lane >> 4, c16 = lane & 15;
-  int blk[4];
+  // The four block ids go through a shared array indexed by the thread id.  As a private array the compiler moves them
+  // to LDS on its own and indexes by a flat thread id that it derives from the dispatch packet: a read of host memory
+  // by every workgroup, 4-15 us at each launch.  (Measured: forms that keep the ids in registers run the layer loop
+  // 4 % slower at identical instruction counts; this form is the one that is fast in both parts.)
+  __shared__ int blk_all[PBLOCK * 4];
+  int* blk = blk_all + threadIdx.x * 4;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int bi = (kbase >> 4) + t;
@@ -1364,7 +1369,14 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   __shared__ int srow[3 * 16];
   __shared__ uint32_t sact[16 * 36];
   __shared__ int sdead;
+#ifdef DF_LDS_PAD
+  __shared__ uint32_t lds_pad[DF_LDS_PAD];
+  if (df_args().tag == 0u) lds_pad[threadIdx.x] = 1u;      // never (launch numbers start at 1)
+#endif
   if (threadIdx.x == 0) sdead = 0;
+#ifdef DF_START_SKEW
+  for (int i = 0; i < (int)(blockIdx.x & 7) * DF_START_SKEW; ++i) __builtin_amdgcn_s_sleep(32);
+#endif
   const int nqkv = (a.nq + 2 * a.nkv) * 64, nqd = a.nq * 64, L = a.n_layers, np = a.d >> 5;
   const int NU = gridDim.x * 2;
   // items of every phase kind, and the unit that takes item 0 (the kinds with few items go to different workgroups)
