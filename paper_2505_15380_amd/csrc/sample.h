@@ -91,7 +91,8 @@ struct WarpArgs {
 };
 
 constexpr int SBLOCK = 1024;          // threads of the two sampler kernels (16 waves): short unrolled loops, small code
-constexpr int SPER = 16;              // elements per thread: vocab <= 16384
+constexpr int SPER = 16;              // elements per thread at most: vocab <= 16384.  The kernels are instantiated for 8 and 16
+                                      // (the loops over a thread's elements are unrolled to that count, so a small vocabulary pays for 8)
 
 // Reductions over the 16 waves of a sampler workgroup through 16 LDS entries; all threads get the result.
 __device__ __forceinline__ float sblock_max(float v, float* s16) {
@@ -117,6 +118,7 @@ __device__ __forceinline__ float sblock_sum(float v, float* s16) {      // fixed
 
 // One workgroup per row.  Top-k keeps exactly k entries: everything above the k-th largest value, and of the
 // entries equal to it the ones with the lowest indices.
+template <int SP>
 __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row) {
   __shared__ float s16[16];
   __shared__ int i16[16];
@@ -128,9 +130,9 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
   float* p = w.probs + (size_t)row * w.probs_stride;
   const int V = w.V;
   // the row is read once into registers (all loads in flight together)
-  float xv[SPER];
+  float xv[SP];
 #pragma unroll
-  for (int e = 0; e < SPER; ++e) {
+  for (int e = 0; e < SP; ++e) {
     const int i = tid + e * SBLOCK;
     xv[e] = i < V ? x[i] : -INFINITY;
   }
@@ -138,7 +140,7 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
   if (w.greedy) {                                            // one-hot at the arg-max, lowest index on ties
     float best = -INFINITY; int bi = 0x7fffffff;
 #pragma unroll
-    for (int e = 0; e < SPER; ++e) { if (xv[e] > best) { best = xv[e]; bi = tid + e * SBLOCK; } }
+    for (int e = 0; e < SP; ++e) { if (xv[e] > best) { best = xv[e]; bi = tid + e * SBLOCK; } }
     const float mx = sblock_max(best, s16);
     int cand = (best == mx) ? bi : 0x7fffffff;
 #pragma unroll
@@ -149,7 +151,7 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
 #pragma unroll
     for (int i = 1; i < 16; ++i) arg = min(arg, i16[i]);
 #pragma unroll
-    for (int e = 0; e < SPER; ++e) {
+    for (int e = 0; e < SP; ++e) {
       const int i = tid + e * SBLOCK;
       if (i < V) p[i] = (i == arg) ? 1.0f : 0.0f;
     }
@@ -169,7 +171,7 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
       const uint32_t prefix = sh_prefix;
       const uint32_t himask = pass ? (0xFFFFFFFFu << (shift + 8)) : 0u;
 #pragma unroll
-      for (int e = 0; e < SPER; ++e) {
+      for (int e = 0; e < SP; ++e) {
         if (tid + e * SBLOCK < V) {
           const uint32_t k = order_key(xv[e]);
           if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
@@ -191,7 +193,7 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
     const int need_eq = sh_krem;                             // entries equal to kth that survive (>= 1)
     int eq = 0;
 #pragma unroll
-    for (int e = 0; e < SPER; ++e) eq += (tid + e * SBLOCK < V && order_key(xv[e]) == kth);
+    for (int e = 0; e < SP; ++e) eq += (tid + e * SBLOCK < V && order_key(xv[e]) == kth);
     eq = wave_sum_i(eq);
     if ((tid & 63) == 0) i16[tid >> 6] = eq;
     __syncthreads();
@@ -210,10 +212,10 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
     }
   }
   const float T = w.temperature;
-  float z[SPER];
+  float z[SP];
   float mx = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < SPER; ++e) {
+  for (int e = 0; e < SP; ++e) {
     const int i = tid + e * SBLOCK;
     z[e] = -INFINITY;
     if (i < V) {
@@ -226,19 +228,20 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
   mx = sblock_max(mx, s16);
   float sum = 0.f;
 #pragma unroll
-  for (int e = 0; e < SPER; ++e) {
+  for (int e = 0; e < SP; ++e) {
     z[e] = (z[e] == -INFINITY) ? 0.f : expf(z[e] - mx);
     sum += z[e];
   }
   sum = sblock_sum(sum, s16);
 #pragma unroll
-  for (int e = 0; e < SPER; ++e) {
+  for (int e = 0; e < SP; ++e) {
     const int i = tid + e * SBLOCK;
     if (i < V) p[i] = z[e] / sum;
   }
 }
 
-__global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) { warp_softmax_row(w, blockIdx.x); }
+template <int SP>
+__global__ void __launch_bounds__(SBLOCK) k_warp_softmax(WarpArgs w) { warp_softmax_row<SP>(w, blockIdx.x); }
 
 // ------------------------------------------------------------------------------ acceptance + resampling
 struct AcceptArgs {
@@ -303,6 +306,7 @@ __device__ __forceinline__ unsigned long long sblock_excl_scan_u64(unsigned long
 //     summation tree): smallest j whose inclusive prefix exceeds floor(total * u).
 //  3. the last workgroup to finish commits every sequence in ascending order: len += pending + n, pending =
 //     emitted token, blocks past the new length go back to the free stack.
+template <int SP>
 __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
   __shared__ unsigned long long w16[16];
   __shared__ int sh_n, sh_tok, sh_last;
@@ -339,23 +343,23 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
   const float u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
   const float* prow = pt + (size_t)n * V;
   const float* drow = pd + (size_t)n * V;                   // only read when n < K
-  const int per = (V + SBLOCK - 1) / SBLOCK;                // contiguous span of indices per thread (<= SPER)
+  const int per = (V + SBLOCK - 1) / SBLOCK;                // contiguous span of indices per thread (<= SP)
   const int j0 = tid * per;
   int fallback = 0;
   bool residual = n < K;
   unsigned long long total, excl, mine;
-  float wgt[SPER];
+  float wgt[SP];
   for (;;) {
     // the thread's span of weights, all loads in flight together
 #pragma unroll
-    for (int e = 0; e < SPER; ++e) {
+    for (int e = 0; e < SP; ++e) {
       const int j = j0 + e;
       wgt[e] = 0.f;
       if (e < per && j < V) wgt[e] = residual ? fmaxf(__fsub_rn(prow[j], drow[j]), 0.f) : prow[j];
     }
     mine = 0;
 #pragma unroll
-    for (int e = 0; e < SPER; ++e) mine += fix40(wgt[e]);
+    for (int e = 0; e < SP; ++e) mine += fix40(wgt[e]);
     excl = sblock_excl_scan_u64(mine, w16, &total);          // sum of the spans before this thread's, and of all
     if (total == 0 && residual) { residual = false; fallback = 1; continue; }
     break;
@@ -370,7 +374,7 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
       int tok = min(j0 + per, V) - 1;
       bool found = false;
 #pragma unroll
-      for (int e = 0; e < SPER; ++e) {
+      for (int e = 0; e < SP; ++e) {
         c += fix40(wgt[e]);
         if (!found && c > tgt) { tok = j0 + e; found = true; }
       }
@@ -426,16 +430,18 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
   a.kv.ctl[2] = 0;
 }
 
-__global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) { accept_seq(a, blockIdx.x); }
+template <int SP>
+__global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) { accept_seq<SP>(a, blockIdx.x); }
 
 // One row per sequence (a draft step, an autoregressive step): the row's distribution and the token drawn from it in
 // one launch.  The probabilities go through memory between the two halves (the caller wants the row anyway, and the
 // halves assign elements to threads differently), so the arithmetic is that of the two kernels above, bit for bit.
+template <int SP>
 __global__ void __launch_bounds__(SBLOCK) k_warp_accept(WarpArgs w, AcceptArgs a) {
-  warp_softmax_row(w, blockIdx.x);
+  warp_softmax_row<SP>(w, blockIdx.x);
   __threadfence_block();
   __syncthreads();
-  accept_seq(a, blockIdx.x);
+  accept_seq<SP>(a, blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------ small state kernels

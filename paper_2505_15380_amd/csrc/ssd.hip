@@ -932,7 +932,8 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
   }
   const bool one_row = probs_last_row_only || (K == 0 && pcap == 1);     // one row per sequence: fused with the sampling
   if (!one_row) {
-    hipLaunchKernelGGL(k_warp_softmax, dim3(M), dim3(SBLOCK), 0, st, w);
+    if (w.V <= 8 * SBLOCK) hipLaunchKernelGGL(k_warp_softmax<8>, dim3(M), dim3(SBLOCK), 0, st, w);
+    else hipLaunchKernelGGL(k_warp_softmax<16>, dim3(M), dim3(SBLOCK), 0, st, w);
     LAUNCH_CHECK();
   }
   a.pd = dev_pd; a.x = dev_x; a.uniforms = nullptr; a.seed = cfg->seed; a.step = step_ctr;
@@ -940,8 +941,14 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
   a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
   a.kv = kv->v; a.seq0 = 0;
   a.slot_base = slot_base;
-  if (one_row) hipLaunchKernelGGL(k_warp_accept, dim3(B), dim3(SBLOCK), 0, st, w, a);
-  else hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, st, a);
+  const bool sp8 = a.V <= 8 * SBLOCK;
+  if (one_row) {
+    if (sp8) hipLaunchKernelGGL(k_warp_accept<8>, dim3(B), dim3(SBLOCK), 0, st, w, a);
+    else hipLaunchKernelGGL(k_warp_accept<16>, dim3(B), dim3(SBLOCK), 0, st, w, a);
+  } else {
+    if (sp8) hipLaunchKernelGGL(k_accept<8>, dim3(B), dim3(SBLOCK), 0, st, a);
+    else hipLaunchKernelGGL(k_accept<16>, dim3(B), dim3(SBLOCK), 0, st, a);
+  }
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -1037,7 +1044,8 @@ extern "C" int ssd_verify_from_probs(const float* dev_pt, const float* dev_pd, c
   a.pt = dev_pt; a.pt_seq_stride = (size_t)(K + 1) * V; a.pd = dev_pd; a.x = dev_tokens; a.uniforms = dev_uniforms;
   a.B = B; a.K = K; a.V = V; a.beta = beta; a.n_acc = dev_n_accepted; a.next_tok = dev_next_token; a.tok_stride = 1;
   a.flags = dev_flags;
-  hipLaunchKernelGGL(k_accept, dim3(B), dim3(SBLOCK), 0, (hipStream_t)stream, a);
+  if (a.V <= 8 * SBLOCK) hipLaunchKernelGGL(k_accept<8>, dim3(B), dim3(SBLOCK), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(k_accept<16>, dim3(B), dim3(SBLOCK), 0, (hipStream_t)stream, a);
   LAUNCH_CHECK();
   return SSD_OK;
 }
@@ -1050,7 +1058,8 @@ extern "C" int ssd_warp_probs(const float* dev_logits, int rows, int V, const ss
   WarpArgs w;
   w.logits = dev_logits; w.ld = V; w.V = V; w.temperature = cfg->temperature; w.top_k = cfg->top_k; w.greedy = cfg->greedy;
   w.probs = dev_probs; w.probs_stride = V;
-  hipLaunchKernelGGL(k_warp_softmax, dim3(rows), dim3(SBLOCK), 0, (hipStream_t)stream, w);
+  if (w.V <= 8 * SBLOCK) hipLaunchKernelGGL(k_warp_softmax<8>, dim3(rows), dim3(SBLOCK), 0, (hipStream_t)stream, w);
+  else hipLaunchKernelGGL(k_warp_softmax<16>, dim3(rows), dim3(SBLOCK), 0, (hipStream_t)stream, w);
   LAUNCH_CHECK();
   return SSD_OK;
 }

@@ -21,7 +21,8 @@ def grid24(a):
 
 
 # ------------------------------------------------------------------------------ acceptance alone (Eq. 5-6)
-@pytest.mark.parametrize("V,K,B", [(7, 1, 3), (512, 4, 8), (6564, 4, 4), (6564, 12, 2), (1000, 0, 5), (257, 15, 3)])
+@pytest.mark.parametrize("V,K,B", [(7, 1, 3), (512, 4, 8), (6564, 4, 4), (6564, 12, 2), (1000, 0, 5), (257, 15, 3),
+                                   (8192, 2, 2), (8193, 2, 2), (16384, 3, 2)])   # both unrolled sizes of the sampler kernels
 @pytest.mark.parametrize("beta", [0.0, 0.4])
 def test_decisions_bit_exact_given_probabilities_and_uniforms(V, K, B, beta):
     import paper_2505_15380_amd as ssd
@@ -73,7 +74,7 @@ def test_decisions_degenerate_rows():
 
 
 # ------------------------------------------------------------------------------ warp + softmax alone
-@pytest.mark.parametrize("V", [512, 6564, 1000])
+@pytest.mark.parametrize("V", [512, 6564, 1000, 8192, 8193, 16384])
 def test_warp_probs_against_oracle(V):
     import paper_2505_15380_amd as ssd
     from oracle.warp import warp_probs
