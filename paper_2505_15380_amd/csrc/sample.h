@@ -119,7 +119,7 @@ __device__ __forceinline__ float sblock_sum(float v, float* s16) {      // fixed
 // One workgroup per row.  Top-k keeps exactly k entries: everything above the k-th largest value, and of the
 // entries equal to it the ones with the lowest indices.
 template <int SP>
-__device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row) {
+__device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row, float* lds_probs = nullptr) {
   __shared__ float s16[16];
   __shared__ int i16[16];
   __shared__ int hist[256];
@@ -153,7 +153,10 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
 #pragma unroll
     for (int e = 0; e < SP; ++e) {
       const int i = tid + e * SBLOCK;
-      if (i < V) p[i] = (i == arg) ? 1.0f : 0.0f;
+      if (i < V) {
+        p[i] = (i == arg) ? 1.0f : 0.0f;
+        if (lds_probs) lds_probs[i] = (i == arg) ? 1.0f : 0.0f;
+      }
     }
     return;
   }
@@ -236,7 +239,11 @@ __device__ __forceinline__ void warp_softmax_row(const WarpArgs w, const int row
 #pragma unroll
   for (int e = 0; e < SP; ++e) {
     const int i = tid + e * SBLOCK;
-    if (i < V) p[i] = z[e] / sum;
+    if (i < V) {
+      const float q = z[e] / sum;
+      p[i] = q;
+      if (lds_probs) lds_probs[i] = q;                        // k_warp_accept: the draw reads the row from LDS
+    }
   }
 }
 
@@ -307,9 +314,10 @@ __device__ __forceinline__ unsigned long long sblock_excl_scan_u64(unsigned long
 //  3. the last workgroup to finish commits every sequence in ascending order: len += pending + n, pending =
 //     emitted token, blocks past the new length go back to the free stack.
 template <int SP>
-__device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
+__device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, const float* lds_row0 = nullptr) {
   __shared__ unsigned long long w16[16];
   __shared__ int sh_n, sh_tok, sh_last;
+  __shared__ float sh_u;
   const int tid = threadIdx.x;
   const int K = a.K, V = a.V;
   const float* pt = a.pt + (size_t)b * a.pt_seq_stride;
@@ -338,10 +346,12 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b) {
     const unsigned long long rej = ~__ballot(acc);          // lanes >= K vote "reject"
     if (tid == 0) sh_n = min(__ffsll((long long)rej) - 1, K);
   }
+  if (tid == WAVE)                                         // the uniform of the draw: one thread of the second wave
+    sh_u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
   __syncthreads();
   const int n = sh_n;
-  const float u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
-  const float* prow = pt + (size_t)n * V;
+  const float u = sh_u;
+  const float* prow = (lds_row0 && n == 0) ? lds_row0 : pt + (size_t)n * V;
   const float* drow = pd + (size_t)n * V;                   // only read when n < K
   const int per = (V + SBLOCK - 1) / SBLOCK;                // contiguous span of indices per thread (<= SP)
   const int j0 = tid * per;
@@ -434,14 +444,17 @@ template <int SP>
 __global__ void __launch_bounds__(SBLOCK) k_accept(AcceptArgs a) { accept_seq<SP>(a, blockIdx.x); }
 
 // One row per sequence (a draft step, an autoregressive step): the row's distribution and the token drawn from it in
-// one launch.  The probabilities go through memory between the two halves (the caller wants the row anyway, and the
-// halves assign elements to threads differently), so the arithmetic is that of the two kernels above, bit for bit.
+// one launch.  The probabilities go to memory (the caller wants the row) and, for the draw, through LDS (the halves
+// assign elements to threads differently); the arithmetic is that of the two kernels above, bit for bit.
 template <int SP>
 __global__ void __launch_bounds__(SBLOCK) k_warp_accept(WarpArgs w, AcceptArgs a) {
-  warp_softmax_row<SP>(w, blockIdx.x);
+  constexpr bool STAGE = SP <= 8;                           // 32 KB of LDS; the larger instantiation re-reads the row from memory
+  __shared__ float row_probs[STAGE ? SP * SBLOCK : 1];
+  float* lds_row = (STAGE && a.K == 0) ? row_probs : nullptr;   // K == 0: the row of the draw is the row just computed
+  warp_softmax_row<SP>(w, blockIdx.x, lds_row);
   __threadfence_block();
   __syncthreads();
-  accept_seq<SP>(a, blockIdx.x);
+  accept_seq<SP>(a, blockIdx.x, lds_row);
 }
 
 // ------------------------------------------------------------------------------------------ small state kernels
