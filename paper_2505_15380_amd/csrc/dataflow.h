@@ -41,7 +41,8 @@ typedef unsigned long long u64;
 #ifndef DF_B_N
 #define DF_B_N 12
 #endif
-constexpr int DF_B = DF_B_N;              // tagged words a thread keeps in flight while it stages operands
+constexpr int DF_B = DF_B_N;              // tagged words a thread keeps in flight while it stages attention operands (and the
+                                          // largest choice for the GEMM operands, see SB below)
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
 constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
 #ifndef DF_NPF_N
@@ -208,6 +209,7 @@ struct DPhase {
 // squares [M][KT] -> sqs.  Thread gt of gn; the whole group polls in parallel.  Two more words per thread (x0, x1:
 // offsets, or ~0) ride in the first flight and come back in xo0, xo1.  Word offsets are recomputed for a repeated
 // load instead of being kept in registers.
+template <int SB>
 __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, int k0, int kn, const u64* sq, int KT,
                                               uint32_t* As, float* sqs, int gt, int gn, uint32_t x0, uint32_t x1,
                                               uint32_t& xo0, uint32_t& xo1, const u64* hint, uint32_t hint_tag) {
@@ -217,10 +219,10 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
   const uint32_t tag = a.tag;
   uint32_t* err = a.bar + 64;
   bool ok = true;
-  for (int base = 0; base < total || base == 0; base += gn * DF_B) {
+  for (int base = 0; base < total || base == 0; base += gn * SB) {
     int g2 = gt;
     auto off_of = [&](int u) -> uint32_t {
-      if (u >= DF_B) return base == 0 ? (u == DF_B ? x0 : x1) : 0xFFFFFFFFu;
+      if (u >= SB) return base == 0 ? (u == SB ? x0 : x1) : 0xFFFFFFFFu;
       const int idx = base + u * gn + g2;
       if (idx < nA) {
         const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
@@ -228,9 +230,9 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
       }
       return idx < total ? s_off + (uint32_t)(idx - nA) : 0xFFFFFFFFu;
     };
-    u64 v[DF_B + 2];
+    u64 v[SB + 2];
 #pragma unroll
-    for (int u = 0; u < DF_B + 2; ++u) {
+    for (int u = 0; u < SB + 2; ++u) {
       const uint32_t o = off_of(u);
       v[u] = o != 0xFFFFFFFFu ? ld_word(a.tw + o) : ((u64)tag << 32);
     }
@@ -238,7 +240,7 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
     for (;;) {
       bool all = true;
 #pragma unroll
-      for (int u = 0; u < DF_B + 2; ++u) all = all && ((uint32_t)(v[u] >> 32) == tag);
+      for (int u = 0; u < SB + 2; ++u) all = all && ((uint32_t)(v[u] >> 32) == tag);
       if (all) break;
       if (spins == 0 && hint) df_wait_hint(hint, hint_tag, err);       // far too early: wait cheaply for the phase before
       if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
@@ -249,11 +251,11 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
       __builtin_amdgcn_s_sleep(1);
       asm volatile("" : "+v"(g2));                       // keeps the offsets out of registers across the wait
 #pragma unroll
-      for (int u = 0; u < DF_B + 2; ++u)
+      for (int u = 0; u < SB + 2; ++u)
         if ((uint32_t)(v[u] >> 32) != tag) v[u] = ld_word(a.tw + off_of(u));
     }
 #pragma unroll
-    for (int u = 0; u < DF_B; ++u) {
+    for (int u = 0; u < SB; ++u) {
       const int idx = base + u * gn + gt;
       if (idx < nA) {
         const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
@@ -262,7 +264,7 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
         sqs[idx - nA] = __uint_as_float((uint32_t)v[u]);
       }
     }
-    if (base == 0) { xo0 = (uint32_t)v[DF_B]; xo1 = (uint32_t)v[DF_B + 1]; }
+    if (base == 0) { xo0 = (uint32_t)v[SB]; xo1 = (uint32_t)v[SB + 1]; }
   }
   return ok;
 }
@@ -291,7 +293,7 @@ __device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU, int 
 // item.  The weight fragments of the unit's item are requested at entry, into registers, before the wait for the
 // operands: units arrive well before their operands do, so the weights' HBM latency is hidden by that wait.
 // Returns true if the workgroup has to leave (timeout somewhere in the grid).
-template <int EPI>
+template <int EPI, int SB>
 __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, uint32_t* lds, const int* srow, int* sdead,
                                               int slot) {
   int tid = threadIdx.x;
@@ -336,7 +338,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
       hx1 = h_off + n1;
     }
     bool ok = true;
-    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -469,6 +471,7 @@ __device__ __forceinline__ void df_prefetch_down(const DArgs& a, const void* wdo
   }
 }
 
+template <int SB>
 __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, const void* wdown, u64* part2, uint32_t tag2,
                                              uint32_t* lds, uint32_t* sact, int* sdead, int slot) {
   int tid = threadIdx.x;
@@ -509,7 +512,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     if ((rd * NU + blockIdx.x * 2) < ph.items) df_prefetch_down(a, wdown, kt2, wd);
     uint32_t dummy0, dummy1;
     bool ok = true;
-    if (rd == 0) ok = stage_operand(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -1361,8 +1364,10 @@ __device__ __forceinline__ const DArgs& df_args() {
   return *(const DArgs*)p;
 }
 
-// WHOLE: attention of short prefixes without parts (df_attn_whole); the host picks the instantiation per launch.
-template <bool WHOLE>
+// WHOLE: attention of short prefixes without parts (df_attn_whole).  SB: tagged words a thread keeps in flight while
+// it stages GEMM operands -- every slot costs instructions whether it is used or not, and a second flight costs a
+// round trip, so the host picks the smallest SB whose single flight (512 threads x SB) holds the launch's rows.
+template <bool WHOLE, int SB>
 __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   const DArgs& a = df_args();
   __shared__ __attribute__((aligned(16))) uint32_t lds[DF_LDS_WORDS];
@@ -1477,7 +1482,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     if (g_q) {
       const DArgs& a = df_args();
       const DPhase cur = make_qkv(a, l);
-      if (df_gemm_phase<PE_QKV>(a, cur, lds, srow, &sdead, s0)) return;
+      if (df_gemm_phase<PE_QKV, SB>(a, cur, lds, srow, &sdead, s0)) return;
     }
     if (g_a) {
       const DArgs& a = df_args();
@@ -1486,13 +1491,13 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     if (g_o) {
       const DArgs& a = df_args();
       const DPhase cur = make_o(a, l);
-      if (df_gemm_phase<PE_RESID>(a, cur, lds, srow, &sdead, s0 + 4)) return;
+      if (df_gemm_phase<PE_RESID, SB>(a, cur, lds, srow, &sdead, s0 + 4)) return;
     }
     if (g_g) {
       const DArgs& a = df_args();
       const DPhase cur = make_swiglu(a, l);
       u64* p2 = a.part2 + (size_t)(l & 1) * a.st_part2;
-      if (df_mlp_phase(a, cur, layer_ptrs(a, l).wdown, p2, df_tag2(a, l), lds, sact, &sdead, s0 + 6)) return;
+      if (df_mlp_phase<SB>(a, cur, layer_ptrs(a, l).wdown, p2, df_tag2(a, l), lds, sact, &sdead, s0 + 6)) return;
     }
     if (g_r) {
       const DArgs& a = df_args();
@@ -1505,7 +1510,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   if (a.with_head && g_l) {
     const DArgs& a = df_args();
     const DPhase cur = make_head(a);
-    df_gemm_phase<PE_LOGITS>(a, cur, lds, srow, &sdead, 2 + L * 10);
+    df_gemm_phase<PE_LOGITS, SB>(a, cur, lds, srow, &sdead, 2 + L * 10);
   }
 }
 

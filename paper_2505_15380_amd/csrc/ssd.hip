@@ -317,6 +317,7 @@ struct ssd_kv {
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel, 4 the same with attention without parts
   bool last_whole = false;
+  int df_sb = 0;             // SSD_DF_FLIGHT=2|4|10|12: words in flight per thread of the operand staging (0: chosen per launch)
   // host
   int32_t* mirror_host;
   std::vector<int> len_ub, npend_ub;
@@ -466,6 +467,9 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
     kv->attn_mfma = !(env && strcmp(env, "valu") == 0);
     env = getenv("SSD_ATTN_WHOLE");
     kv->attn_whole = env ? (env[0] == '1' || (env[0] == '2' && pending_cap == 2)) : (pending_cap == 2);
+    env = getenv("SSD_DF_FLIGHT");
+    kv->df_sb = env ? atoi(env) : 0;
+    if (kv->df_sb != 2 && kv->df_sb != 4 && kv->df_sb != 10 && kv->df_sb != 12) kv->df_sb = 0;
     env = getenv("SSD_GEMM");
     kv->gemm_wide = !(env && strcmp(env, "narrow") == 0);
     kv->narrow_down = env && strcmp(env, "narrow_down") == 0;
@@ -718,8 +722,13 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.trace = kv->trace_on ? kv->trace : nullptr;
   ProfScope ps(PROF_PERSISTENT, st);
   kv->last_whole = whole;
-  if (whole) hipLaunchKernelGGL(k_forward_dataflow<true>, dim3(G), dim3(PBLOCK), 0, st, a);
-  else hipLaunchKernelGGL(k_forward_dataflow<false>, dim3(G), dim3(PBLOCK), 0, st, a);
+  // words of one operand staging: the rows' operand words and their sums of squares; one flight holds 512 x SB
+  const int stage_words = M * (std::max(c.d_model, nqd) + c.d_model / 32);
+  const int sb = kv->df_sb ? kv->df_sb : stage_words <= 2 * PBLOCK ? 2 : stage_words <= 4 * PBLOCK ? 4 : stage_words <= 10 * PBLOCK ? 10 : 12;
+#define DF_LAUNCH(W, S) hipLaunchKernelGGL((k_forward_dataflow<W, S>), dim3(G), dim3(PBLOCK), 0, st, a)
+  if (whole) { if (sb == 2) DF_LAUNCH(true, 2); else if (sb == 4) DF_LAUNCH(true, 4); else DF_LAUNCH(true, 12); }
+  else { if (sb == 2) DF_LAUNCH(false, 2); else if (sb == 4) DF_LAUNCH(false, 4); else if (sb == 10) DF_LAUNCH(false, 10); else DF_LAUNCH(false, 12); }
+#undef DF_LAUNCH
   LAUNCH_CHECK();
   return SSD_OK;
 }

@@ -142,6 +142,21 @@ def test_mini_bf16_attention_without_parts(n_prefix, K, monkeypatch):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("flight,K", [("2", 0), ("2", 12), ("4", 4), ("10", 12), ("12", 0), ("", 1), ("", 3)])
+def test_mini_bf16_operand_staging_flights(flight, K, monkeypatch):
+    """The barrier-free kernel is instantiated per number of tagged words a thread keeps in flight while it stages GEMM
+    operands (chosen per launch from the row count): every size with rows that fit one flight and rows that need
+    several, and the launch's own choice."""
+    from tests.parity import run_verify_parity
+    if flight:
+        monkeypatch.setenv("SSD_DF_FLIGHT", flight)
+    else:
+        monkeypatch.delenv("SSD_DF_FLIGHT", raising=False)
+    r = run_verify_parity("mini", steps=3, K=K, beta=0.3, atol_logits=2e-2, atol_probs=2e-2)
+    assert r["path"] == 3, "the barrier-free persistent kernel did not run"
+
+
+@pytest.mark.gpu
 def test_barrier_and_barrier_free_kernels_agree(monkeypatch):
     """Same model, prefix and drafts through both persistent kernels: logits agree to rounding (they share the
     arithmetic definitions but not every summation order), decisions given equal probabilities are covered above."""
