@@ -205,15 +205,16 @@ struct DPhase {
   float* logits;          // PE_LOGITS
 };
 
-// Operand words [k0, k0+kn) of rows [0, M) (row stride K words) -> As[row * (kn + 4) + k - k0], and the rows' sums of
+// Operand words of rows [0, M) (K words each, the rows contiguous) -> As[row * (K + 4) + k], and the rows' sums of
 // squares [M][KT] -> sqs.  Thread gt of gn; the whole group polls in parallel.  Two more words per thread (x0, x1:
 // offsets, or ~0) ride in the first flight and come back in xo0, xo1.  Word offsets are recomputed for a repeated
-// load instead of being kept in registers.
+// load instead of being kept in registers; with whole rows a word's offset is its index, and only the padded LDS
+// address needs the row (every slot of a flight costs its instructions whether it holds a word or not).
 template <int SB>
-__device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, int k0, int kn, const u64* sq, int KT,
+__device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, const u64* sq, int KT,
                                               uint32_t* As, float* sqs, int gt, int gn, uint32_t x0, uint32_t x1,
                                               uint32_t& xo0, uint32_t& xo1, const u64* hint, uint32_t hint_tag) {
-  const int M = a.rows.M, nA = M * kn, total = nA + (sq ? M * KT : 0), stride = kn + 4;
+  const int M = a.rows.M, kn = K, nA = M * kn, total = nA + (sq ? M * KT : 0);
   const uint32_t a_off = (uint32_t)(A - a.tw), s_off = sq ? (uint32_t)(sq - a.tw) : 0u;
   const float rkn = 1.0f / (float)kn;
   const uint32_t tag = a.tag;
@@ -224,10 +225,7 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
     auto off_of = [&](int u) -> uint32_t {
       if (u >= SB) return base == 0 ? (u == SB ? x0 : x1) : 0xFFFFFFFFu;
       const int idx = base + u * gn + g2;
-      if (idx < nA) {
-        const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
-        return a_off + (uint32_t)(row * K + k0 + k);
-      }
+      if (idx < nA) return a_off + (uint32_t)idx;
       return idx < total ? s_off + (uint32_t)(idx - nA) : 0xFFFFFFFFu;
     };
     u64 v[SB + 2];
@@ -258,8 +256,8 @@ __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int 
     for (int u = 0; u < SB; ++u) {
       const int idx = base + u * gn + gt;
       if (idx < nA) {
-        const int row = (int)(((float)idx + 0.5f) * rkn), k = idx - row * kn;
-        As[row * stride + k] = (uint32_t)v[u];
+        const int row = (int)(((float)idx + 0.5f) * rkn);
+        As[idx + 4 * row] = (uint32_t)v[u];
       } else if (idx < total) {
         sqs[idx - nA] = __uint_as_float((uint32_t)v[u]);
       }
@@ -338,7 +336,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
       hx1 = h_off + n1;
     }
     bool ok = true;
-    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -512,7 +510,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     if ((rd * NU + blockIdx.x * 2) < ph.items) df_prefetch_down(a, wdown, kt2, wd);
     uint32_t dummy0, dummy1;
     bool ok = true;
-    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, 0, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
