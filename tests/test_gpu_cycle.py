@@ -41,13 +41,16 @@ def test_ssd_cycles_in_lockstep_with_oracle(workload, tol, beta):
     """Draft steps (Eq. 2-3) and verification (Eq. 4-6) over several cycles, including the two-token catch-up
     after a fully accepted cycle.  Every draft distribution and target distribution is compared; every drawn
     token and decision must equal the oracle's canonical rule applied to the GPU's own fp32 probabilities."""
+    run_cycles_in_lockstep(workload, tol, beta, K=3, steps=10, require_both=True)
+
+
+def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix=40, sharp_steps=True):
     import paper_2505_15380_amd as ssd
     from oracle import decoder as OD, ssd as OS
     from oracle.accept import sample_canonical, accept_canonical
     from oracle.philox import uniform24
     from oracle.warp import warp_probs
-    K, steps = 3, 10
-    sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos) = make_session(workload, K, beta=beta, steps=steps)
+    sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos) = make_session(workload, K, beta=beta, steps=steps, n_prefix=n_prefix)
     t, d = OD.Model(ts, tw), OD.Model(ds, dw)
     tc, dc = OD.Cache(ts, max_pos), OD.Cache(ds, max_pos)
     OD.prefill(t, tc, toks[:-1]); OD.prefill(d, dc, toks[:-1])
@@ -56,7 +59,8 @@ def test_ssd_cycles_in_lockstep_with_oracle(workload, tol, beta):
     seen_full = seen_reject = False
     for step in range(steps):
         # alternate a flat and a sharp temperature so that full acceptance and rejection both occur
-        cfg["temperature"] = dcfg["temperature"] = 1.0 if step % 2 == 0 else 0.05
+        # (a temperature of 0.05 multiplies the logits' error by 20: only where the tolerance has that room)
+        cfg["temperature"] = dcfg["temperature"] = 1.0 if (step % 2 == 0 or not sharp_steps) else 0.05
         sess.cfg, sess.dcfg = ssd.sample_config(**cfg), ssd.sample_config(**dcfg)
         out = dict(n_accepted=torch.zeros(1, dtype=torch.int32, device="cuda"),
                    next_token=torch.zeros(1, dtype=torch.int32, device="cuda"),
@@ -87,7 +91,8 @@ def test_ssd_cycles_in_lockstep_with_oracle(workload, tol, beta):
         st, sd = sess.kv.state(0), sess.kv_d.state(0)
         assert st["len"] == tc.length and st["pending"] == [pending]
         assert sd["len"] == dc.length and sd["pending"] == dpend
-    assert seen_reject and seen_full
+    assert (seen_reject and seen_full) or not require_both
+    return sess
 
 
 @pytest.mark.parametrize("workload", ["tiny", "mini"])

@@ -130,3 +130,16 @@ def test_one_half_b_batch8_sampled_parity():
     # oracle is met within 4e-2 only; against the oracle with the same cache format the arithmetic must hold 2e-2
     path = _sampled_batch_parity("one_half_b_batch8", sample=(0,), atol=2e-2, atol_exact=4e-2)
     assert path == 1
+
+
+@pytest.mark.timeout(900)
+def test_half_b_cycles_in_lockstep_full_size():
+    """Whole SSD cycles of the benchmark's configuration (24-layer target, 4-layer draft, prefix 1024, K = 4) in lockstep
+    with the oracle: the draft's one- and two-row steps on its cache with two pending slots (attention without parts), the
+    verification, the draft cache following the decision -- the launches bench.py times, each distribution compared."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests.test_gpu_cycle import run_cycles_in_lockstep
+    sess = run_cycles_in_lockstep("half_b_k4", 2e-2, 0.4, K=4, steps=6, require_both=True, n_prefix=1019,
+                                  sharp_steps=False)                          # 5 + 1019 = 1024 tokens, the workload's temperature
+    assert sess.kv.last_forward_path() == 3 and sess.kv_d.last_forward_path() == 4
