@@ -155,6 +155,34 @@ def test_batched_ragged_verify_parity(workload, tol):
     assert len({tuple(n) for n in ns}) > 1 and any(len(set(n)) > 1 for n in ns)
 
 
+def test_many_sequences_reserve_blocks_in_one_launch():
+    """Eight sequences x two rows = 16 rows on the barrier-free kernel, whose reservation takes one lane per sequence:
+    lengths chosen so that in the same launch some sequences need no new block, some one, and several at once; the
+    block tables and the order of the free stack must follow the serial allocator model through every step."""
+    from tests.parity import Pair, verify_parity_step
+    wl = si.workload("mini")
+    shape = si.model_shape(wl["target"])
+    B, K, steps = 8, 1, 10
+    lens = [15, 16, 17, 30, 31, 32, 47, 9]             # block size 16: boundaries are crossed at different steps, often together
+    pair = Pair(wl["target"], wl["seeds"]["target"], 47 + steps * (K + 1) + 20, max_seqs=B, max_rows=2,
+                n_blocks=B * 5 + 1, block_tokens=16)
+    for b in range(B):
+        pair.prefill(b, si.make_prefix(shape, 2, lens[b] - 2, 700 + b))
+    pair.check_free_stack()
+    rng = np.random.default_rng(11)
+    cfg = dict(beta=0.3, temperature=1.0, top_k=0, greedy=False, seed=99)
+    together = 0
+    for s in range(steps):
+        owned_before = [pair.alloc.owned[b] for b in range(B)]
+        verify_parity_step(pair, cfg, K, s, rng, 2e-2, 2e-2, seqs=tuple(range(B)))
+        assert pair.kv.last_forward_path() == 3
+        for b in range(B):
+            pair.check_state(b, 2e-2, layers=[shape["n_layers"] - 1])
+        pair.check_free_stack()
+        together = max(together, sum(pair.alloc.owned[b] != owned_before[b] for b in range(B)))
+    assert together >= 2                                  # at least once several sequences changed their block count in one step
+
+
 def test_batched_verify_beyond_one_row_tile_uses_matrix_core_attention():
     """Five ragged sequences x (K+1 = 5) rows = 25 rows: more than the persistent kernels take, so every operator is
     its own launch and attention runs as 256-key parts on the matrix cores.  Lengths put new positions on both sides
