@@ -155,6 +155,72 @@ def test_batched_ragged_verify_parity(workload, tol):
     assert len({tuple(n) for n in ns}) > 1 and any(len(set(n)) > 1 for n in ns)
 
 
+@pytest.mark.parametrize("B,K,target_path", [(4, 3, 3), (16, 2, 1)])
+def test_batched_cycles_in_lockstep_with_oracle(B, K, target_path):
+    """Whole SSD cycles of several sequences at once: after a verification some sequences have one pending draft row and
+    some two (everything accepted), so one draft launch mixes active and inactive rows, the draft caches roll back by
+    different amounts, and every sequence is followed by an oracle of its own.  Four sequences stay on the persistent
+    kernels throughout; sixteen have 16-row draft steps there, 32-row first steps and the verification per operator."""
+    import paper_2505_15380_amd as ssd
+    from oracle import decoder as OD, ssd as OS
+    from oracle.accept import sample_canonical
+    from oracle.philox import uniform24
+    from oracle.warp import warp_probs
+    wl = si.workload("mini")
+    ts, ds = si.model_shape(wl["target"]), si.model_shape(wl["draft"])
+    tw, dw = si.make_weights(ts, wl["seeds"]["target"]), si.make_weights(ds, wl["seeds"]["draft"])
+    steps, tol = 8, 2e-2
+    lens = [21, 40, 33, 64, 17, 90, 48, 31, 16, 75, 52, 29, 63, 44, 36, 81][:B]
+    toks = [si.make_prefix(ts, 4, n - 4, 500 + b) for b, n in enumerate(lens)]
+    cfg = dict(beta=0.5, temperature=1.0, top_k=0, greedy=False, seed=31)
+    dcfg = dict(beta=0.0, temperature=1.0, top_k=0, greedy=False, seed=32)
+    max_pos = max(lens) + steps * (K + 1) + 40
+    sess = ssd.SSDSession(ts, tw, ds, dw, B, K, max_pos, ssd.sample_config(**cfg), ssd.sample_config(**dcfg))
+    t, d = OD.Model(ts, tw), OD.Model(ds, dw)
+    tc, dc, pending, dpend = [], [], [], []
+    for b in range(B):
+        sess.prefill(b, torch.from_numpy(toks[b]).cuda())
+        tc.append(OD.Cache(ts, max_pos)); dc.append(OD.Cache(ds, max_pos))
+        OD.prefill(t, tc[b], toks[b][:-1]); OD.prefill(d, dc[b], toks[b][:-1])
+        pending.append(int(toks[b][-1])); dpend.append([int(toks[b][-1])])
+    V = ts["vocab"]
+    mixed = False
+    for step in range(steps):
+        out = dict(n_accepted=torch.zeros(B, dtype=torch.int32, device="cuda"),
+                   next_token=torch.zeros(B, dtype=torch.int32, device="cuda"),
+                   probs=torch.zeros((B, K + 1, V), dtype=torch.float32, device="cuda"), logits=None)
+        sess.cycle(step, out=out)
+        torch.cuda.synchronize()
+        assert sess.kv.last_forward_path() == target_path and sess.kv_d.last_forward_path() in (3, 4)
+        gx, gpd, gp = sess.x.cpu().numpy(), sess.pd.cpu().numpy(), out["probs"].cpu().numpy()
+        ns = []
+        for b in range(B):
+            for i in range(K):                            # the oracle's draft steps, teacher-forced with the GPU's tokens
+                lg = OD.forward_rows(d, dc[b], dpend[b])
+                dc[b].length += len(dpend[b])
+                ref = warp_probs(lg[-1:], dcfg["temperature"])[0]
+                assert np.abs(gpd[b, i] - ref).max() <= tol, (step, b, i)
+                tok = sample_canonical(gpd[b, i], uniform24(dcfg["seed"], b, step, i))
+                assert tok == int(gx[b, i]), (step, b, i)
+                dpend[b] = [tok]
+            r, u = OS.verify_uniforms(cfg["seed"], b, step, K)
+            L = tc[b].length
+            res = OS.verify_step(t, tc[b], pending[b], list(gx[b]), gpd[b], OS.sample_cfg(**cfg), r, u, pt32=gp[b])
+            assert np.abs(gp[b] - res["pt"]).max() <= tol, (step, b)
+            assert (int(out["n_accepted"][b]), int(out["next_token"][b])) == (res["n"], res["next"]), (step, b)
+            n, pending[b] = res["n"], res["next"]
+            ns.append(n)
+            if n < K:
+                dc[b].length = L + 1 + n; dpend[b] = [pending[b]]
+            else:
+                dpend[b] = [int(gx[b, -1]), pending[b]]
+            st, sd = sess.kv.state(b), sess.kv_d.state(b)
+            assert st["len"] == tc[b].length and st["pending"] == [pending[b]], (step, b)
+            assert sd["len"] == dc[b].length and sd["pending"] == dpend[b], (step, b)
+        mixed = mixed or (K in ns and any(n < K for n in ns))
+    assert mixed                                          # one and two pending draft rows occurred in the same launch
+
+
 def test_many_sequences_reserve_blocks_in_one_launch():
     """Eight sequences x two rows = 16 rows on the barrier-free kernel, whose reservation takes one lane per sequence:
     lengths chosen so that in the same launch some sequences need no new block, some one, and several at once; the
