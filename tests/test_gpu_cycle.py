@@ -57,6 +57,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
     pending, dpend = int(toks[-1]), [int(toks[-1])]
     V = ts["vocab"]
     seen_full = seen_reject = False
+    draft_paths = set()
     for step in range(steps):
         # alternate a flat and a sharp temperature so that full acceptance and rejection both occur
         # (a temperature of 0.05 multiplies the logits' error by 20: only where the tolerance has that room)
@@ -67,6 +68,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
                    probs=torch.zeros((1, K + 1, V), dtype=torch.float32, device="cuda"), logits=None)
         sess.cycle(step, out=out)
         torch.cuda.synchronize()
+        draft_paths.add(sess.kv_d.last_forward_path())
         gx, gpd = sess.x.cpu().numpy()[0], sess.pd.cpu().numpy()[0]
         # oracle draft steps, teacher-forced with the GPU's tokens
         for i in range(K):
@@ -92,6 +94,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
         assert st["len"] == tc.length and st["pending"] == [pending]
         assert sd["len"] == dc.length and sd["pending"] == dpend
     assert (seen_reject and seen_full) or not require_both
+    sess.draft_paths_seen = draft_paths
     return sess
 
 
@@ -153,6 +156,14 @@ def test_batched_ragged_verify_parity(workload, tol):
             pair.check_state(b, tol, layers=[shape["n_layers"] - 1])
         pair.check_free_stack()
     assert len({tuple(n) for n in ns}) > 1 and any(len(set(n)) > 1 for n in ns)
+
+
+def test_draft_attention_mode_changes_with_the_prefix():
+    """The draft's launches take attention without parts while the host's bound of the cached length allows it (1520
+    positions) and attention in parts beyond: cycles in lockstep with the oracle across that length."""
+    sess = run_cycles_in_lockstep("mini", 2e-2, 0.4, K=3, steps=12, require_both=False, n_prefix=1490)
+    assert sess.draft_paths_seen == {3, 4}
+    assert sess.kv_d.state(0)["len"] > 1520
 
 
 @pytest.mark.parametrize("B,K,target_path", [(4, 3, 3), (16, 2, 1)])
