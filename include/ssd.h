@@ -43,6 +43,7 @@ extern "C" {
 #define SSD_DTYPE_FP32 0
 #define SSD_DTYPE_BF16 1
 #define SSD_MAX_K      15  /* draft tokens per cycle */
+#define SSD_DRAFT_SLOT0 (SSD_MAX_K + 1)  /* first random-counter slot of the draft's draws (see ssd_sample_config) */
 
 typedef struct ssd_model ssd_model;   /* a decoder: shape + device weights in the layout the kernels stream */
 typedef struct ssd_kv    ssd_kv;      /* a paged KV cache + per-sequence state + activation workspace    */
@@ -61,7 +62,10 @@ typedef struct {
 /* Sampling of one model.  pt and pd are post-warp distributions: logits / temperature, then top-k
  * (ties at the k-th value: lower index survives), then softmax; greedy != 0 replaces the row by a one-hot
  * at the arg-max (lowest index).  Uniforms come from Philox-4x32-10 keyed by `seed` with counter
- * (slot, sequence, step_lo, step_hi): slots 0..K-1 are r_1..r_K, slot K draws the emitted token. */
+ * (slot, sequence, step_lo, step_hi).  A verification uses slots 0..K-1 for r_1..r_K and slot K for the emitted
+ * token; draft step i of the same cycle draws x_{i+1} with slot SSD_DRAFT_SLOT0 + i.  Eq. 5 compares r_i with a
+ * ratio that depends on x_i, and Alg. 1 draws r_i afresh, so the two must be independent: with the slot ranges
+ * disjoint they are even when draft and target are given the same seed. */
 typedef struct {
   float    beta;          /* tolerance factor of Eq. 5, >= 0 (used by ssd_verify only) */
   float    temperature;   /* > 0 */
@@ -108,7 +112,7 @@ int ssd_prefill(ssd_model* m, ssd_kv* kv, int seq, const int32_t* dev_tokens, in
 /* ---- the three calls of the hot path ------------------------------------------------------------------
  * ssd_draft_step (Eq. 2-3): for sequences 0..n_seqs-1 of the draft cache feed the pending token(s), give the
  * warped distribution pd (full fp32 row, written to dev_probs_out + b*probs_stride) and a token drawn
- * from it with uniform slot `draft_idx` (written to dev_token_out[b*token_stride]); the token becomes the
+ * from it with uniform slot SSD_DRAFT_SLOT0 + draft_idx (written to dev_token_out[b*token_stride]); the token becomes the
  * new pending token and the length grows by the rows fed.  Strides are in elements. */
 int ssd_draft_step(ssd_model* draft, ssd_kv* kv_d, int n_seqs, const ssd_sample_config* cfg,
                    uint64_t step_ctr, int draft_idx, int32_t* dev_token_out, int token_stride,
@@ -133,7 +137,10 @@ int ssd_verify(ssd_model* target, ssd_kv* kv, int n_seqs, const int32_t* prefix_
                float* dev_target_probs_opt, float* dev_logits_opt, void* stream);
 
 /* ssd_kv_rollback: truncate sequence `seq` to `new_len` cached positions (<= its current length), free the
- * blocks wholly past it and set the single pending token.  Used for the draft cache after a rejection. */
+ * blocks wholly past it and set the single pending token.  Used for the draft cache after a rejection.
+ * The length lives on the device and the call does not wait for it: a new_len beyond the host's upper bound of the
+ * length is refused at once (SSD_EINVAL); one between the device's length and that bound is refused by the kernel -
+ * the sequence stays as it was - and the NEXT call on this cache returns SSD_EINVAL (see ssd_kv_clear_error). */
 int ssd_kv_rollback(ssd_kv* kv, int seq, int new_len, int pending_token, void* stream);
 
 /* Device-side form for the draft cache after a verify of K >= 1 drafts, no host round trip: for each
@@ -141,6 +148,27 @@ int ssd_kv_rollback(ssd_kv* kv, int seq, int new_len, int pending_token, void* s
  * [x_K, next_token] (x_K was sampled but never fed to the draft). */
 int ssd_kv_follow(ssd_kv* kv_d, int n_seqs, int K, const int32_t* dev_n_accepted,
                   const int32_t* dev_next_token, const int32_t* dev_draft_tokens, void* stream);
+
+/* ---- one SSD cycle as a replayable graph (Alg. 1 loop body) ---------------------------------------------------
+ * K draft steps (Eq. 2-3), the verification (Eq. 4-6) and the draft cache following the decision, captured once as
+ * a HIP graph and replayed by ssd_cycle_launch: nothing a replay needs is a kernel argument that changes from cycle
+ * to cycle (the cycle index of the random counter and the launch numbers of the forward kernels are read from
+ * device memory and advanced by the cycle's own kernels).  The caller's buffers (dev_draft_tokens [n_seqs,K],
+ * dev_draft_probs [n_seqs,K,V], dev_n_accepted [n_seqs], dev_next_token [n_seqs]) are rewritten by every replay and
+ * must outlive the handle.  The cycle index starts at first_step.  Launch shapes are captured for lengths up to 256
+ * positions beyond the current ones; ssd_cycle_launch captures again (synchronising the stream) when the host's
+ * bound of a length outgrows that, so a replay never runs with a stale shape.  Both caches must run the barrier-free
+ * forward kernel (bf16 storage, head_dim 64, at most 16 rows per launch), else SSD_ENOSUP.  `stream` of
+ * ssd_cycle_launch must not be the default (NULL) stream, which HIP cannot capture (SSD_EINVAL).  Between replays
+ * the caches may be used through the other calls as well, on the same stream. */
+typedef struct ssd_cycle ssd_cycle;
+int ssd_cycle_create(ssd_model* target, ssd_kv* kv, ssd_model* draft, ssd_kv* kv_d, int n_seqs, int K,
+                     const ssd_sample_config* cfg, const ssd_sample_config* dcfg, int32_t* dev_draft_tokens,
+                     float* dev_draft_probs, int32_t* dev_n_accepted, int32_t* dev_next_token, uint64_t first_step,
+                     void* stream, ssd_cycle** out);
+int ssd_cycle_launch(ssd_cycle* c, void* stream);
+int ssd_cycle_captures(const ssd_cycle* c);     /* how many times the graph has been captured so far */
+int ssd_cycle_destroy(ssd_cycle* c);
 
 /* ---- the acceptance step alone (Eq. 5-6), for decision parity with given probabilities and uniforms ----
  * dev_pt [B, K+1, V], dev_pd [B, K, V], dev_tokens [B, K], dev_uniforms [B, K+1] (r_1..r_K then the
@@ -160,10 +188,32 @@ int ssd_warp_probs(const float* dev_logits, int rows, int V, const ssd_sample_co
  * ceil((len+R)/block_tokens) blocks, popping the free stack; a commit or rollback to new_len pushes back the
  * blocks with table index >= ceil(new_len/block_tokens), highest index first.  `free_stack` is returned bottom
  * first (the last entry is popped next).  dev_error_flag: bit 0 = the device allocator ran out of blocks, bit 1 = a
- * wait inside a persistent kernel timed out (the cache is unusable afterwards).  Any output pointer may be NULL. */
+ * persistent forward kernel gave up (a bounded wait timed out, or the launch numbering ran out), bit 2 = a rollback
+ * beyond the cached length was refused.  Any output pointer may be NULL. */
 int ssd_kv_state(ssd_kv* kv, int seq, void* stream, int32_t* len, int32_t* n_pending, int32_t pending[2],
                  int32_t* n_owned, int32_t* block_table, int block_table_cap);
 int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, int cap, int32_t* n_free, int32_t* dev_error_flag);
+
+/* ---- errors raised on the device ------------------------------------------------------------------------------
+ * Every wait inside the persistent forward kernels is bounded.  When one gives up, every workgroup leaves, the
+ * kernel that follows the forward commits NOTHING (lengths, pending tokens and blocks stay as they were; the
+ * outputs of that call are void) and the error reaches the host through a host-mapped word: the next call on that
+ * cache - and every one after it - returns SSD_EHIP until ssd_kv_clear_error.  The same path reports a refused
+ * rollback (SSD_EINVAL), pool exhaustion found by the device allocator (SSD_ENOMEM), and an exhausted launch
+ * numbering (SSD_EHIP; the library renumbers by itself long before that unless its calls are replayed from a graph
+ * it did not capture).  ssd_kv_clear_error re-zeroes the words the kernels synchronise through, clears the flags
+ * and restarts the numbering, in stream order; sequence state is kept.  Not allowed inside a stream capture. */
+int ssd_kv_clear_error(ssd_kv* kv, void* stream);
+
+/* Test hooks: force, from the host, conditions that otherwise need a fault.  SSD_HOOK_TIMEOUT raises the device's
+ * timeout word, so that every bounded wait of later forwards gives up at once and all kernels still exit normally.
+ * SSD_HOOK_LAUNCH_NUMBER sets the number the next forward on the cache reads (1 .. 2^25-2), on device and host;
+ * SSD_HOOK_LAUNCH_NUMBER_DEVICE_ONLY sets it on the device alone (up to 2^25-1, the value at which forwards refuse
+ * to run), as a graph replayed past the limit would leave it. */
+#define SSD_HOOK_TIMEOUT 1
+#define SSD_HOOK_LAUNCH_NUMBER 2
+#define SSD_HOOK_LAUNCH_NUMBER_DEVICE_ONLY 3
+int ssd_kv_test_hook(ssd_kv* kv, int what, long long value, void* stream);
 
 /* ---- measurement ---------------------------------------------------------------------------------------
  * Between ssd_profile_begin(kind) and ssd_profile_end() every launch of the named kernel family is bracketed
@@ -179,12 +229,14 @@ int ssd_profile_end(double* total_ms, int* launches);
  * 0 none yet, 1 one launch per operator (fp32 storage, more than 16 rows, head_dim other than 64),
  * 2 one persistent kernel with grid barriers between phases, 3 one persistent kernel whose phases are ordered by
  * tagged data words (the default for bf16 storage and at most 16 rows; the environment variable
- * SSD_FORWARD=barrier, read at ssd_kv_create, selects 2 instead), 4 the same kernel with the attention of a short prefix
+ * SSD_FORWARD=barrier, read at ssd_kv_create, selects 2 instead; 2 is also what runs when a launch exceeds the
+ * limits of 3), 4 the same kernel with the attention of a short prefix
  * (at most 1520 cached positions) done by one workgroup per row tile instead of 256-key parts (the default for caches
  * created with pending_cap 2; SSD_ATTN_WHOLE=1 selects it for every cache, 0 for none). */
 int ssd_kv_last_forward_path(const ssd_kv* kv);
 
-/* Phase trace of the persistent forward kernels: with enable != 0 every later forward on `kv` records, per
+/* Phase trace of the persistent forward kernels, recorded only by builds with -DSSD_TRACE (otherwise SSD_ENOSUP
+ * and the kernels carry no clock reads): with enable != 0 every later forward on `kv` records, per
  * workgroup, 100 MHz wall-clock samples.  When `out` is non-NULL the samples of the last forward are copied out
  * first (synchronises `stream`): rows of 512 entries per workgroup, *n_wgs workgroups, cap >= 512 * workgroups.
  * Barrier kernel: out[wg*512 + 2*b] = arrival and [.. + 2*b+1] = release of grid barrier b for b < *n_samples / 2.

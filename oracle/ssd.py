@@ -10,9 +10,19 @@ def sample_cfg(beta=0.0, temperature=1.0, top_k=0, greedy=False, seed=0):
     return dict(beta=beta, temperature=temperature, top_k=top_k, greedy=greedy, seed=seed)
 
 
+DRAFT_SLOT0 = 16   # first slot of the draft's draws: past every slot a verification can use (K <= 15)
+
+
 def verify_uniforms(seed, seq, step, K):
     """r_1..r_K (slots 0..K-1) and the sampling uniform (slot K) of one verify step."""
     return [uniform24(seed, seq, step, i) for i in range(K)], uniform24(seed, seq, step, K)
+
+
+def draft_uniform(seed, seq, step, i):
+    """The uniform that draws x_{i+1} ~ pd_{i+1} (Eq. 3).  Eq. 5 needs r_i independent of the draw of x_i
+    (Alg. 1 draws r ~ U[0,1] afresh), so the draft's draws have slots of their own: a caller may give both
+    models one seed."""
+    return uniform24(seed, seq, step, DRAFT_SLOT0 + i)
 
 
 def verify_step(model, cache, pending, x, pd, cfg, r, u, pt32=None):
@@ -61,7 +71,7 @@ def ssd_generate(target, draft, tcache, dcache, pending, K, cfg, dcfg, n_tokens,
     while len(out) < n_tokens and (max_cycles is None or step < max_cycles):
         xs, pds = [], []
         for i in range(K):
-            tok, pd = draft_step(draft, dcache, dpend, dcfg, uniform24(dcfg["seed"], seq, step, i))
+            tok, pd = draft_step(draft, dcache, dpend, dcfg, draft_uniform(dcfg["seed"], seq, step, i))
             xs.append(tok)
             pds.append(pd)
             dpend = [tok]

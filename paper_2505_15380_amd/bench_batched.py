@@ -25,7 +25,12 @@ def main():
     ap.add_argument("--cycles", type=int, default=0)
     ap.add_argument("--beta", type=float, default=0.2)
     args = ap.parse_args()
+    print(json.dumps(measure(args)))
 
+
+def measure(args, weights=None):
+    """The record of one batched workload (args: workload, iters, cycles, beta).  `weights`: the target's tensors when the
+    caller has them already."""
     import numpy as np
     import torch
     import paper_2505_15380_amd as ssd
@@ -33,7 +38,7 @@ def main():
 
     wl = si.workload(args.workload)
     shape = si.model_shape(wl["target"])
-    w = si.make_weights(shape, wl["seeds"]["target"])
+    w = weights if weights is not None else si.make_weights(shape, wl["seeds"]["target"])
     B, K = wl["batch"], wl["K"]
     rng = np.random.default_rng(wl["seeds"]["prefix"])
     lo, hi = wl["prefix_range"]
@@ -127,7 +132,7 @@ def main():
                "mean_accepted_per_sequence_and_cycle": round(float(n_acc.mean()), 3),
                "accepted_min_max_in_one_cycle": [int(n_acc.min()), int(n_acc.max())],
                "draft_forward_path": sess.kv_d.last_forward_path(), "target_forward_path": sess.kv.last_forward_path()}
-    print(json.dumps({
+    return ({
         "workload": args.workload, "batch": B, "K": K, "rows": rows, "prefix_lengths": sorted(lens),
         "forward_path": fwd_path, "verify_us": round(t_ms * 1e3, 1), "per_operator": per_kind,
         "weight_bytes": weight_bytes, "kv_bytes": kv_bytes, "gemm_flops": gemm_flops, "attention_flops": attn_flops,
@@ -136,7 +141,7 @@ def main():
         "achieved_GBps": round((weight_bytes + kv_bytes) / (t_ms * 1e-3) / 1e9, 1),
         "frac_of_hbm_peak": round((weight_bytes + kv_bytes) / (t_ms * 1e-3) / 8e12, 4),
         "verified_rows_per_s": round(rows / (t_ms * 1e-3), 1), "ssd_cycles": cyc,
-    }))
+    })
 
 
 if __name__ == "__main__":

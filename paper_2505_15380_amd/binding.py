@@ -11,6 +11,7 @@ EXPORTED_SYMBOLS = [
     "ssd_kv_workspace_bytes", "ssd_kv_create", "ssd_kv_destroy", "ssd_prefill", "ssd_draft_step", "ssd_verify",
     "ssd_kv_rollback", "ssd_kv_follow", "ssd_verify_from_probs", "ssd_warp_probs", "ssd_kv_state",
     "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_kv_last_forward_path", "ssd_trace_barriers", "ssd_strerror", "ssd_last_error",
+    "ssd_kv_clear_error", "ssd_kv_test_hook", "ssd_cycle_create", "ssd_cycle_launch", "ssd_cycle_captures", "ssd_cycle_destroy",
 ]
 
 
@@ -75,6 +76,13 @@ def load_library():
         "ssd_profile_end": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_int)]),
         "ssd_kv_last_forward_path": (i32, [vp]),
         "ssd_trace_barriers": (i32, [vp, i32, vp, C.POINTER(C.c_uint64), i32, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
+        "ssd_kv_clear_error": (i32, [vp, vp]),
+        "ssd_kv_test_hook": (i32, [vp, i32, C.c_longlong, vp]),
+        "ssd_cycle_create": (i32, [vp, vp, vp, vp, i32, i32, C.POINTER(SampleConfig), C.POINTER(SampleConfig), i32p, f32p,
+                                   i32p, i32p, u64, vp, C.POINTER(vp)]),
+        "ssd_cycle_launch": (i32, [vp, vp]),
+        "ssd_cycle_captures": (i32, [vp]),
+        "ssd_cycle_destroy": (i32, [vp]),
         "ssd_strerror": (C.c_char_p, [i32]),
         "ssd_last_error": (C.c_char_p, []),
     }
@@ -193,8 +201,15 @@ class KVCache:
                     n_owned=own.value, table=list(table)[:own.value])
 
     def last_forward_path(self):
-        """1 one launch per operator, 2 persistent kernel with grid barriers, 3 barrier-free persistent kernel."""
+        """1 one launch per operator, 2 persistent kernel with grid barriers, 3 barrier-free persistent kernel,
+        4 the same with the attention of a short prefix done without parts."""
         return load_library().ssd_kv_last_forward_path(self.handle)
+
+    def clear_error(self):
+        _check(load_library().ssd_kv_clear_error(self.handle, _stream()))
+
+    def test_hook(self, what, value=0):
+        _check(load_library().ssd_kv_test_hook(self.handle, int(what), int(value), _stream()))
 
     def free_stack(self):
         lib = load_library()
@@ -265,6 +280,37 @@ def ssd_kv_follow(kv_d, n_seqs, K, n_accepted, next_token, draft_tokens):
     assert n_accepted.dtype == next_token.dtype == draft_tokens.dtype == torch.int32
     _check(load_library().ssd_kv_follow(kv_d.handle, n_seqs, K, _ptr(n_accepted), _ptr(next_token),
                                         _ptr(draft_tokens), _stream()))
+
+
+HOOK_TIMEOUT, HOOK_LAUNCH_NUMBER, HOOK_LAUNCH_NUMBER_DEVICE_ONLY = 1, 2, 3
+
+
+class Cycle:
+    """ssd_cycle handle: one SSD cycle captured as a graph; launch() replays it on the current stream."""
+
+    def __init__(self, target, kv, draft, kv_d, n_seqs, K, cfg, dcfg, draft_tokens, draft_probs, n_accepted, next_token,
+                 first_step=0):
+        for t, dt in ((draft_tokens, torch.int32), (draft_probs, torch.float32), (n_accepted, torch.int32),
+                      (next_token, torch.int32)):
+            assert t.dtype == dt and t.is_cuda and t.is_contiguous()
+        assert draft_tokens.numel() == n_seqs * K and draft_probs.numel() == n_seqs * K * target.shape["vocab"]
+        self._keep = (target, kv, draft, kv_d, draft_tokens, draft_probs, n_accepted, next_token)
+        h = C.c_void_p()
+        _check(load_library().ssd_cycle_create(target.handle, kv.handle, draft.handle, kv_d.handle, n_seqs, K, C.byref(cfg),
+                                               C.byref(dcfg), _ptr(draft_tokens), _ptr(draft_probs), _ptr(n_accepted),
+                                               _ptr(next_token), int(first_step), _stream(), C.byref(h)))
+        self.handle = h
+
+    def launch(self):
+        _check(load_library().ssd_cycle_launch(self.handle, _stream()))
+
+    def captures(self):
+        return load_library().ssd_cycle_captures(self.handle)
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _LIB is not None:
+            _LIB.ssd_cycle_destroy(self.handle)
+            self.handle = None
 
 
 def ssd_verify_from_probs(pt, pd, tokens, uniforms, beta):

@@ -106,12 +106,24 @@ struct KvView {
   int32_t* owned;      // [max_seqs] blocks owned
   int32_t* table;      // [max_seqs][mbps] block ids
   int32_t* free_stack; // [n_blocks]
-  int32_t* ctl;        // [0] free_top  [1] error flag  [2] arrival counter of the accept kernel
-  int32_t* mirror;     // host-mapped copy: [max_seqs][2] = (len, n_pend), then [2*max_seqs] = error flag
+  int32_t* ctl;        // [0] free_top  [1] state error bits (KV_ERR_*)  [2] arrival counter of the accept kernel
+                       // [3] number of the next forward launch on this cache (the tag of its hand-over words)
+                       // [4],[5] cycle counter of a captured cycle (low, high word of the random counter's step)
+  uint32_t* err;       // sticky error word of the persistent forward kernels: DEV_ERR_* bits
+  int32_t* mirror;     // host-mapped copy: [max_seqs][2] = (len, n_pend), then [2*max_seqs] = ctl[1], [2*max_seqs+1] = *err
   void* pool;
   int n_blocks, bt, mbps, max_seqs, pcap;
   int n_layers, nkv, hd;
 };
+
+constexpr int KV_ERR_POOL = 1;        // the device allocator ran out of blocks
+constexpr int KV_ERR_ROLLBACK = 4;    // a rollback asked for more positions than the sequence holds (refused)
+constexpr uint32_t DEV_ERR_TIMEOUT = 1u;   // a bounded wait inside a persistent forward gave up
+constexpr uint32_t DEV_ERR_TAGS = 2u;      // the launch counter reached its limit: the tagged workspace must be cleared
+// Launch numbers tag the hand-over words of the barrier-free forward; the MLP partials carry launch * 128 + layer in
+// 32 bits, so launch numbers stay below 2^25.  The host clears the workspace and restarts the numbering before that;
+// a forward that still finds the limit reached does nothing and raises DEV_ERR_TAGS.
+constexpr uint32_t TAG_LIMIT = (1u << 25) - 1u;
 
 // Element offset of (layer, which(0=K,1=V), block, kv head, token in block, 0) in the pool.  Keys are stored
 // [token][dim]; values [dim][token], so for values only tok == 0 (the head's base) is meaningful here.
@@ -198,10 +210,19 @@ __device__ inline void kv_truncate(const KvView& kv, int seq, int new_len) {
   kv.len[seq] = new_len;
 }
 
+__device__ inline void kv_publish_flags(const KvView& kv) {
+  kv.mirror[2 * kv.max_seqs] = kv.ctl[1];
+  kv.mirror[2 * kv.max_seqs + 1] = (int32_t)*kv.err;
+}
 __device__ inline void kv_publish(const KvView& kv, int seq) {
   kv.mirror[2 * seq] = kv.len[seq];
   kv.mirror[2 * seq + 1] = kv.n_pend[seq];
-  kv.mirror[2 * kv.max_seqs] = kv.ctl[1];
+  kv_publish_flags(kv);
+}
+// After a forward: the next launch on this cache gets the next number (one thread, the kernel that follows the forward).
+__device__ inline void kv_bump_launch(const KvView& kv) {
+  const uint32_t t = (uint32_t)kv.ctl[3] + 1u;
+  kv.ctl[3] = (int32_t)t;
 }
 
 // Rows of one forward: row m belongs to sequence seq0 + m / R at offset j = m % R.

@@ -17,8 +17,9 @@
 // bf16 whose sum the matrix core consumes); residual rows, sums of squares and partial results are fp32 bits; new
 // keys / values are bf16 bits.
 //
-// A workgroup stages the operand rows it needs in LDS once (all its threads poll in parallel, 14 words in flight
-// each) and feeds the matrix cores from LDS.  The weights of an item are requested at the entry of its phase, into
+// A workgroup stages the operand rows it needs in LDS once (all its threads poll in parallel, SB words in flight
+// each: the kernel is instantiated for SB = 2, 4, 10, 12 and the host picks the smallest that holds the launch's rows
+// in one flight) and feeds the matrix cores from LDS.  The weights of an item are requested at the entry of its phase, into
 // registers, before that wait: workgroups arrive at a phase before its operands do, so the wait hides the HBM latency.
 // The phases with few items (QKV, attention, output projection) run on workgroups of their own, beyond those that
 // take the MLP items, so that no workgroup is late for the MLP, the phase every workgroup waits for.
@@ -30,25 +31,23 @@
 // key / value fragments from that buffer at the same fragment slots the pool would have supplied, so a row's bits
 // do not depend on how many rows are verified together.
 //
-// One grid barrier remains, after phase 0 (row bookkeeping and block reservation), once per launch.
-// All waits are bounded; a timeout raises the error flag and every workgroup leaves.
+// There is no grid barrier: phase 0 (row bookkeeping, embedding, block reservation) hands over like every other phase.
+// All waits are bounded; a timeout raises the error word and every workgroup leaves; the kernel that follows the
+// forward then commits nothing and copies the word to the host-mapped mirror, where the next call on the cache finds it.
+//
+// The launch number is not a kernel argument: it is read from the cache's control words, and the kernel that follows
+// every forward on the stream advances it, so a captured graph of launches can be replayed.
 #pragma once
 #include "persistent.h"
 
 namespace ssd {
 
 typedef unsigned long long u64;
-#ifndef DF_B_N
-#define DF_B_N 12
-#endif
-constexpr int DF_B = DF_B_N;              // tagged words a thread keeps in flight while it stages attention operands (and the
+constexpr int DF_B = 12;                  // tagged words a thread keeps in flight while it stages attention operands (and the
                                           // largest choice for the GEMM operands, see SB below)
 constexpr int DF_AW = 21504;              // LDS words of the operand staging area (84 KB)
 constexpr int DF_ATT_ROWS = 256;          // query rows of a sequence (rows x heads of a group): at most 16 tiles of 16
-#ifndef DF_NPF_N
-#define DF_NPF_N 5
-#endif
-constexpr int DF_NPF = DF_NPF_N;          // attention parts merged per flight
+constexpr int DF_NPF = 5;                 // attention parts merged per flight
 constexpr long DF_SPIN_LIMIT = 1L << 18;
 // LDS words: staging | sums of squares | unit reduction buffers, overlaid by the attention buffers of the two units
 constexpr int DF_SQ_WORDS = 1024;
@@ -57,15 +56,9 @@ constexpr int DF_ATT_UNIT = 4096 + 512 + 512 + 4096 + 4096 + 128;      // Q | ne
 constexpr int DF_LDS_WORDS = (DF_AW + DF_SQ_WORDS + DF_RED_WORDS) > 2 * DF_ATT_UNIT ? (DF_AW + DF_SQ_WORDS + DF_RED_WORDS)
                                                                                   : 2 * DF_ATT_UNIT;
 
-#ifndef DF_HINT_OWN
-#define DF_HINT_OWN 9      // bit k set: phase kind k (0 QKV, 1 attention, 2 O, 3 MLP, 4 sum) watches a word of its OWN operands
-#endif
-#ifndef DF_HINT_SLEEP
-#define DF_HINT_SLEEP 2
-#endif
-#ifndef DF_HINT_LAST
-#define DF_HINT_LAST 1
-#endif
+// Which single word a wave watches after a failed first flight (see df_wait_hint): the phases with many consumers (QKV,
+// MLP) watch a word of their OWN operands, the others a word of the preceding phase's operands.
+constexpr int DF_HINT_SLEEP = 2;
 
 struct DArgs {
   int n_layers, d, nq, nkv, ffn, vocab, n_embed;
@@ -80,7 +73,6 @@ struct DArgs {
   Rows rows;
   int pcap, n_seqs, tok_stride, with_head;
   const int32_t* tokens;
-  uint32_t tag;           // this launch's number: the upper half of every word written by it
   u64* tw;                // base of the tagged workspace; the members below point into it
   u64* h;                 // [2L+1][PR][d]      fp32: residual stream entering layer l at 2l, after attention at 2l+1
   u64* hg;                // [2L+1][PR][d]      operand: h times the gain of the RMSNorm that consumes it
@@ -213,11 +205,11 @@ struct DPhase {
 template <int SB>
 __device__ __forceinline__ bool stage_operand(const DArgs& a, const u64* A, int K, const u64* sq, int KT,
                                               uint32_t* As, float* sqs, int gt, int gn, uint32_t x0, uint32_t x1,
-                                              uint32_t& xo0, uint32_t& xo1, const u64* hint, uint32_t hint_tag) {
+                                              uint32_t& xo0, uint32_t& xo1, const u64* hint, uint32_t hint_tag,
+                                              const uint32_t tag) {
   const int M = a.rows.M, kn = K, nA = M * kn, total = nA + (sq ? M * KT : 0);
   const uint32_t a_off = (uint32_t)(A - a.tw), s_off = sq ? (uint32_t)(sq - a.tw) : 0u;
   const float rkn = 1.0f / (float)kn;
-  const uint32_t tag = a.tag;
   uint32_t* err = a.bar + 64;
   bool ok = true;
   for (int base = 0; base < total || base == 0; base += gn * SB) {
@@ -276,7 +268,12 @@ __device__ __forceinline__ void frag_from_lds(const uint32_t* p, u32x4& hi, u32x
              __builtin_amdgcn_perm(w1[1], w1[0], 0x07060302u), __builtin_amdgcn_perm(w1[3], w1[2], 0x07060302u)};
 }
 
+// Clock samples per workgroup and phase, only in builds with -DSSD_TRACE (see ssd_trace_barriers).
+#ifdef SSD_TRACE
 #define DF_STAMP(slot) do { if (a.trace && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * 512 + (slot)] = wall_clock64(); } while (0)
+#else
+#define DF_STAMP(slot) do { } while (0)
+#endif
 
 // Item of round 0 that `unit` takes when items start at unit `shift` and take every `stride`-th unit (stride 2: one
 // item per workgroup, its other unit idles, so the item's waves have their SIMDs to themselves); a huge number where none.
@@ -292,8 +289,8 @@ __device__ __forceinline__ int df_item_of_unit(int unit, int shift, int NU, int 
 // operands: units arrive well before their operands do, so the weights' HBM latency is hidden by that wait.
 // Returns true if the workgroup has to leave (timeout somewhere in the grid).
 template <int EPI, int SB>
-__device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, uint32_t* lds, const int* srow, int* sdead,
-                                              int slot) {
+__device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const uint32_t tag, const DPhase& ph, uint32_t* lds,
+                                              const int* srow, int* sdead, int slot) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -336,7 +333,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
       hx1 = h_off + n1;
     }
     bool ok = true;
-    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, hx0, hx1, hv0, hv1, ph.hint, ph.hint_tag, tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -401,15 +398,15 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
         }
         if (head < a.nq) {
           u64* qo = ph.out + (size_t)row * (a.nq * 64) + head * 64 + dd;
-          st_word(qo, split_payload(v0), a.tag);
-          st_word(qo + 32, split_payload(v1), a.tag);
+          st_word(qo, split_payload(v0), tag);
+          st_word(qo + 32, split_payload(v1), tag);
         } else {
           const int which = head < a.nq + a.nkv ? 0 : 1;
           const int kvh = head - a.nq - which * a.nkv;
           const bf16_t b0 = f_to_bf16(v0), b1 = f_to_bf16(v1);
           u64* ko = ph.kvn + ((size_t)row * 2 + which) * (a.nkv * 64) + kvh * 64 + dd;
-          st_word(ko, b0, a.tag);
-          st_word(ko + 32, b1, a.tag);
+          st_word(ko, b0, tag);
+          st_word(ko + 32, b1, tag);
           if (active && rblk >= 0) {
             bf16_t* base = (bf16_t*)a.kv.pool + kv_offset(a.kv, ph.layer, which, rblk, kvh, 0);
             const int tok = pos & 15;
@@ -430,14 +427,14 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
         if (row < M) {
           v0 += __uint_as_float(hv0);
           v1 += __uint_as_float(hv1);
-          st_wordf(ph.h_out + (size_t)row * ph.N + n0, v0, a.tag);
-          st_wordf(ph.h_out + (size_t)row * ph.N + n1, v1, a.tag);
-          st_word(ph.hg_out + (size_t)row * ph.N + n0, split_payload(v0 * gn0), a.tag);
-          st_word(ph.hg_out + (size_t)row * ph.N + n1, split_payload(v1 * gn1), a.tag);
+          st_wordf(ph.h_out + (size_t)row * ph.N + n0, v0, tag);
+          st_wordf(ph.h_out + (size_t)row * ph.N + n1, v1, tag);
+          st_word(ph.hg_out + (size_t)row * ph.N + n0, split_payload(v0 * gn0), tag);
+          st_word(ph.hg_out + (size_t)row * ph.N + n1, split_payload(v1 * gn1), tag);
           q2 = v0 * v0 + v1 * v1;
         }
         q2 = row16_sum(q2);
-        if (col == 0 && row < M) st_wordf(ph.sq_out + (size_t)row * (ph.N >> 5) + pair, q2, a.tag);
+        if (col == 0 && row < M) st_wordf(ph.sq_out + (size_t)row * (ph.N >> 5) + pair, q2, tag);
       }
     }
     if (rd == 0) DF_STAMP(slot + 1);
@@ -454,7 +451,7 @@ __device__ __forceinline__ bool df_gemm_phase(const DArgs& a, const DPhase& ph, 
 constexpr int DF_DN = 7;                  // down-projection output tiles a wave keeps prefetched
 struct WDown { u32x4 b[DF_DN]; };
 
-__device__ __forceinline__ uint32_t df_tag2(const DArgs& a, int layer) { return a.tag * 128u + (uint32_t)layer; }
+__device__ __forceinline__ uint32_t df_tag2(const uint32_t tag, int layer) { return tag * 128u + (uint32_t)layer; }
 
 // Fragments (n-tile wave + 8 i, k-tile kt2) of the down projection for i < DF_DN; exactly DF_DN loads.
 __device__ __forceinline__ void df_prefetch_down(const DArgs& a, const void* wdown, int kt2, WDown& wd) {
@@ -470,7 +467,7 @@ __device__ __forceinline__ void df_prefetch_down(const DArgs& a, const void* wdo
 }
 
 template <int SB>
-__device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, const void* wdown, u64* part2, uint32_t tag2,
+__device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const uint32_t tag, const DPhase& ph, const void* wdown, u64* part2, uint32_t tag2,
                                              uint32_t* lds, uint32_t* sact, int* sdead, int slot) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
@@ -510,7 +507,7 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
     if ((rd * NU + blockIdx.x * 2) < ph.items) df_prefetch_down(a, wdown, kt2, wd);
     uint32_t dummy0, dummy1;
     bool ok = true;
-    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag);
+    if (rd == 0) ok = stage_operand<SB>(a, ph.A, ph.K, ph.sq, KT, As, sqs, tid, PBLOCK, 0xFFFFFFFFu, 0xFFFFFFFFu, dummy0, dummy1, ph.hint, ph.hint_tag, tag);
     if (!ok) *sdead = 1;
     __syncthreads();
     if (*sdead) return true;
@@ -595,11 +592,8 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const DPhase& ph, c
 // Sum of the ffn/32 down-projection partials in ascending order, residual, and the operand / statistics of the next
 // RMSNorm.  Task = (row, 32 output columns); thread (column c, group g of 8) sums the partials of its group, the
 // groups meet in LDS in ascending order.
-#ifndef DF_RW_N
-#define DF_RW_N 20
-#endif
-constexpr int DF_RW = DF_RW_N;            // partials a thread keeps in flight
-__device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const u64* part2, uint32_t tag2, const u64* h_in,
+constexpr int DF_RW = 20;                 // partials a thread keeps in flight
+__device__ __forceinline__ bool df_reduce_phase(const DArgs& a, const uint32_t tag, int layer, const u64* part2, uint32_t tag2, const u64* h_in,
                                                 u64* h_out, u64* hg_out, u64* sq_out, const float* gain_next, int shift,
                                                 uint32_t* lds, int* sdead, int slot) {
   int tid = threadIdx.x;
@@ -622,7 +616,7 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
     const u64* src = part2 + ((size_t)w0 * PR + m) * d + 32 * p + c;
     const size_t wstride = (size_t)PR * d;
     float sum = 0.f;
-    u64 hw = (u64)a.tag << 32;
+    u64 hw = (u64)tag << 32;
     const bool want_h = valid && grp == 0;
     for (int b0 = 0; b0 < cnt || (b0 == 0 && want_h); b0 += DF_RW) {
       u64 v[DF_RW];
@@ -631,15 +625,12 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
       if (b0 == 0 && want_h) hw = ld_word(h_in + (size_t)m * d + 32 * p + c);
       long spins = 0;
       for (;;) {
-        bool all = (uint32_t)(hw >> 32) == a.tag;
+        bool all = (uint32_t)(hw >> 32) == tag;
 #pragma unroll
         for (int i = 0; i < DF_RW; ++i) all = all && ((uint32_t)(v[i] >> 32) == tag2);
         if (all) break;
         // a workgroup that comes here from its own MLP item is not early: no hint for it
-        if (spins == 0 && (int)blockIdx.x >= a.g_mlp) {
-          if (DF_HINT_OWN & 16) df_wait_hint(part2, tag2, err);
-          else df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, a.tag, err);
-        }
+        if (spins == 0 && (int)blockIdx.x >= a.g_mlp) df_wait_hint(a.hg + (size_t)(2 * layer + 1) * a.st_h, tag, err);
         if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, AG) != 0)) {
           __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, AG);
           bad = true;
@@ -649,7 +640,7 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 #pragma unroll
         for (int i = 0; i < DF_RW; ++i)
           if ((uint32_t)(v[i] >> 32) != tag2) v[i] = ld_word(src + (size_t)(b0 + i) * wstride);
-        if ((uint32_t)(hw >> 32) != a.tag) hw = ld_word(h_in + (size_t)m * d + 32 * p + c);
+        if ((uint32_t)(hw >> 32) != tag) hw = ld_word(h_in + (size_t)m * d + 32 * p + c);
       }
 #pragma unroll
       for (int i = 0; i < DF_RW; ++i)
@@ -666,12 +657,12 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
       for (int gq = 1; gq < 8; ++gq) v += rs[gq * 32 + c];
       v += __uint_as_float((uint32_t)hw);
       const size_t o = (size_t)m * d + 32 * p + c;
-      st_wordf(h_out + o, v, a.tag);
-      st_word(hg_out + o, split_payload(v * gain_next[32 * p + c]), a.tag);
+      st_wordf(h_out + o, v, tag);
+      st_word(hg_out + o, split_payload(v * gain_next[32 * p + c]), tag);
       float q2 = v * v;
 #pragma unroll
       for (int off = 16; off > 0; off >>= 1) q2 += __shfl_xor(q2, off, 32);
-      if (c == 0) st_wordf(sq_out + (size_t)m * np + p, q2, a.tag);
+      if (c == 0) st_wordf(sq_out + (size_t)m * np + p, q2, tag);
     }
     if (rd == 0) DF_STAMP(slot + 1);
     __syncthreads();
@@ -681,7 +672,7 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, int layer, const
 
 // ------------------------------------------------------------------------------------------------ phase 0
 // Rows and embedding.  Item = row.
-__device__ __forceinline__ void df_embed_phase(const DArgs& a) {
+__device__ __forceinline__ void df_embed_phase(const DArgs& a, const uint32_t tag) {
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), usel = wave >> 2, ut = tid & 255;
   const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
   const int M = a.rows.M, R = a.rows.R, d = a.d;
@@ -708,12 +699,12 @@ __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
     for (int p = ut >> 5; p < (d >> 5); p += 8) {
       const int c = p * 32 + (ut & 31);
       const float v = bf16_to_f(src[c]);
-      st_wordf(a.h + (size_t)m * d + c, v, a.tag);
-      st_word(a.hg + (size_t)m * d + c, split_payload(v * gain[c]), a.tag);
+      st_wordf(a.h + (size_t)m * d + c, v, tag);
+      st_word(a.hg + (size_t)m * d + c, split_payload(v * gain[c]), tag);
       float sq = v * v;
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, WAVE);
-      if ((ut & 31) == 0) st_wordf(a.sq + (size_t)m * (d >> 5) + p, sq, a.tag);
+      if ((ut & 31) == 0) st_wordf(a.sq + (size_t)m * (d >> 5) + p, sq, tag);
     }
   }
 }
@@ -725,7 +716,9 @@ __device__ __forceinline__ void df_embed_phase(const DArgs& a) {
 // key goes out as a tagged word per row (the workgroups with QKV items, whose epilogue appends the keys and values,
 // wait for it once), and attention never reads a position of this launch from the pool.  The launch therefore has no
 // grid barrier.
-__device__ __forceinline__ void df_reserve_blocks(const DArgs& a) {
+__device__ __forceinline__ bool df_tag_ok(uint32_t tag) { return tag != 0u && tag < TAG_LIMIT; }
+
+__device__ __forceinline__ void df_reserve_blocks(const DArgs& a, const int tag_v) {
   if (blockIdx.x != 0 || threadIdx.x >= 64) return;
   const int b = threadIdx.x, R = a.rows.R;
   const bool on = b < a.n_seqs;
@@ -736,6 +729,8 @@ __device__ __forceinline__ void df_reserve_blocks(const DArgs& a) {
   const int own = ld_state(a.kv.owned + s);
   const int off = a.pcap ? a.pcap - np_s : 0;
   const int need = ceil_div(len_s + R - off, a.kv.bt);
+  const uint32_t tag = (uint32_t)__builtin_amdgcn_readfirstlane(tag_v);
+  if (!df_tag_ok(tag)) return;                                     // a refused launch changes nothing
   const int want = on ? max(0, need - own) : 0, room = max(0, a.kv.mbps - own);
   const int take = min(want, room);
   int before = take;                                               // blocks that lower sequences take: exclusive prefix sum
@@ -769,7 +764,7 @@ __device__ __forceinline__ void df_reserve_blocks(const DArgs& a) {
       const int pos = j < off ? len_s : len_s + (j - off);
       const int bi = pos >> 4;
       const int v = bi == bi0 ? id[0] : bi == bi0 + 1 ? id[1] : -1;
-      st_word(a.rowblk + b * R + j, (uint32_t)v, a.tag);
+      st_word(a.rowblk + b * R + j, (uint32_t)v, tag);
     }
   }
   if (b == 0) a.kv.ctl[0] = max(0, top - total);
@@ -865,7 +860,7 @@ __device__ __forceinline__ void df_load_kv(const DArgs& a, int layer, const DAtt
 __device__ __forceinline__ float df_exp2(float x) { return __builtin_amdgcn_exp2f(x); }     // x <= 0 here, or -inf
 
 
-__device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const DAttItem& it, uint32_t* lds,
+__device__ __forceinline__ bool df_attn_phase(const DArgs& a, const uint32_t tag, int layer, const DAttItem& it, uint32_t* lds,
                                               const int* srow, int* sdead, int slot) {
   // The pool fragments are requested first: the queries of this layer are not there yet in any case.
   KVPre kvp;
@@ -917,7 +912,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
       }
     }
-    bad = !poll_words<DF_B>(a.tw, off, a.tag, out, a.bar + 64, (DF_HINT_OWN & 2) ? q + (size_t)(it.b * R) * nqd + (it.kvh * G) * 64 : a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
+    bad = !poll_words<DF_B>(a.tw, off, tag, out, a.bar + 64, a.hg + (size_t)(2 * layer) * a.st_h, tag);
 #pragma unroll
     for (int u = 0; u < DF_B; ++u) {
       const int idx = u * 256 + ut;
@@ -1041,13 +1036,13 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         }
         if (np_row == 1) {                                  // a single part: this is the result
 #pragma unroll
-          for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+          for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), tag);
         } else {
           u64* pp = att_p + ((((size_t)m * a.nq + head) * a.NP + it.part) * 16 + ch) * 6;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) st_wordf(pp + i, o[i], a.tag);
-          st_wordf(pp + 4, mx, a.tag);
-          st_wordf(pp + 5, l, a.tag);
+          for (int i = 0; i < 4; ++i) st_wordf(pp + i, o[i], tag);
+          st_wordf(pp + 4, mx, tag);
+          st_wordf(pp + 5, l, tag);
         }
       }
     }
@@ -1066,7 +1061,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
         float mx = -INFINITY, l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
         for (int p0 = 0; p0 < np_row; p0 += DF_NPF) {
           uint32_t out[DF_NPF * 6];
-          bad = !poll_parts(a.tw, p_off + (uint32_t)(p0 * 96), np_row - p0, a.tag, out, a.bar + 64) || bad;
+          bad = !poll_parts(a.tw, p_off + (uint32_t)(p0 * 96), np_row - p0, tag, out, a.bar + 64) || bad;
           float gm = mx;
 #pragma unroll
           for (int p = 0; p < DF_NPF; ++p)
@@ -1088,7 +1083,7 @@ __device__ __forceinline__ bool df_attn_phase(const DArgs& a, int layer, const D
             }
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+        for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), tag);
       }
     }
   }
@@ -1157,7 +1152,7 @@ __device__ __forceinline__ void df_load_kv_chunk(const DArgs& a, int layer, int 
   }
 }
 
-__device__ __forceinline__ bool df_attn_whole(const DArgs& a, int layer, const DAttWhole& it, uint32_t* lds, const int* sblk,
+__device__ __forceinline__ bool df_attn_whole(const DArgs& a, const uint32_t tag, int layer, const DAttWhole& it, uint32_t* lds, const int* sblk,
                                               const int* srow, int* sdead, int slot) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
@@ -1206,7 +1201,7 @@ __device__ __forceinline__ bool df_attn_whole(const DArgs& a, int layer, const D
         off[u] = n_off + (uint32_t)((((it.b * R + it.off + jn) * 2 + which) * a.nkv + it.kvh) * 64 + dd);
       }
     }
-    bad = !poll_words<NB>(a.tw, off, a.tag, out, a.bar + 64, (DF_HINT_OWN & 2) ? q + (size_t)(it.b * R) * nqd + (it.kvh * G) * 64 : a.hg + (size_t)(2 * layer) * a.st_h, a.tag);
+    bad = !poll_words<NB>(a.tw, off, tag, out, a.bar + 64, a.hg + (size_t)(2 * layer) * a.st_h, tag);
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const int idx = u * PBLOCK + tid;
@@ -1343,7 +1338,7 @@ __device__ __forceinline__ bool df_attn_whole(const DArgs& a, int layer, const D
         for (int i = 0; i < 4; ++i) o[i] = fmaf(MO[(w * 16 + row) * 64 + d0 + i], e, o[i]);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), a.tag);
+      for (int i = 0; i < 4; ++i) st_word(attn + (size_t)m * nqd + head * 64 + d0 + i, split_payload(o[i] / l), tag);
     }
   }
   DF_STAMP(slot + 1);
@@ -1372,14 +1367,11 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   __shared__ int srow[3 * 16];
   __shared__ uint32_t sact[16 * 36];
   __shared__ int sdead;
-#ifdef DF_LDS_PAD
-  __shared__ uint32_t lds_pad[DF_LDS_PAD];
-  if (df_args().tag == 0u) lds_pad[threadIdx.x] = 1u;      // never (launch numbers start at 1)
-#endif
   if (threadIdx.x == 0) sdead = 0;
-#ifdef DF_START_SKEW
-  for (int i = 0; i < (int)(blockIdx.x & 7) * DF_START_SKEW; ++i) __builtin_amdgcn_s_sleep(32);
-#endif
+  // this launch's number (the kernel that follows a forward on the stream advances the word; nothing in this launch
+  // does).  Requested first, looked at after the other start-up loads have been requested.
+  const int tag_v = ld_state(a.kv.ctl + 3);
+  uint32_t tag = 0u;
   const int nqkv = (a.nq + 2 * a.nkv) * 64, nqd = a.nq * 64, L = a.n_layers, np = a.d >> 5;
   const int NU = gridDim.x * 2;
   // items of every phase kind, and the unit that takes item 0 (the kinds with few items go to different workgroups)
@@ -1395,12 +1387,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     x.layer = l; x.A = a.hg + (size_t)(2 * l) * a.st_h; x.sq = a.sq + (size_t)(2 * l) * a.st_sq;
     x.W0 = Y.wqkv; x.W1 = Y.wqkv; x.N = nqkv; x.K = a.d; x.gs = 1; x.items = n_qkv; x.shift = s_qkv; x.stride = st;
     x.bias = Y.bqkv; x.out = a.q + (size_t)l * a.st_q; x.kvn = a.kvn + (size_t)l * a.st_kvn;
-#if DF_HINT_LAST
-    if (DF_HINT_OWN & 1) { x.hint = x.A + (size_t)(a.rows.M - 1) * a.d + (a.d - 32); x.hint_tag = a.tag; }   // a word of the last sum task
-#else
-    if (DF_HINT_OWN & 1) { x.hint = x.A; x.hint_tag = a.tag; }
-#endif
-    else if (l > 0) { x.hint = a.part2 + (size_t)((l - 1) & 1) * a.st_part2; x.hint_tag = df_tag2(a, l - 1); }
+    x.hint = x.A + (size_t)(a.rows.M - 1) * a.d + (a.d - 32); x.hint_tag = tag;   // a word of the last sum task
     return x;
   };
   auto make_o = [&](const DArgs& a, int l) {
@@ -1413,8 +1400,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     x.h_in = a.h + hi * a.st_h; x.h_out = a.h + (hi + 1) * a.st_h; x.hg_out = a.hg + (hi + 1) * a.st_h;
     x.sq_out = a.sq + (hi + 1) * a.st_sq;
     x.gain_next = Y.ln2;
-    if (DF_HINT_OWN & 4) { x.hint = x.A; x.hint_tag = a.tag; }
-    else { x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = a.tag; }
+    x.hint = a.q + (size_t)l * a.st_q; x.hint_tag = tag;
     return x;
   };
   auto make_swiglu = [&](const DArgs& a, int l) {
@@ -1422,8 +1408,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     DPhase x = DPhase{};
     x.layer = l; x.A = a.hg + (size_t)(2 * l + 1) * a.st_h; x.sq = a.sq + (size_t)(2 * l + 1) * a.st_sq;
     x.W0 = Y.wgate; x.W1 = Y.wup; x.N = a.ffn; x.K = a.d; x.gs = 1; x.items = n_gu; x.shift = 0; x.stride = 1;
-    if (DF_HINT_OWN & 8) { x.hint = a.hg + (size_t)(2 * l + 1) * a.st_h; x.hint_tag = a.tag; }
-    else { x.hint = a.attn + (size_t)l * a.st_q; x.hint_tag = a.tag; }
+    x.hint = a.hg + (size_t)(2 * l + 1) * a.st_h; x.hint_tag = tag;
     return x;
   };
   auto make_head = [&](const DArgs& a) {
@@ -1444,7 +1429,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
              g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
 
   DF_STAMP(1);
-  df_reserve_blocks(a);
+  df_reserve_blocks(a, tag_v);
   // What the launch needs of the cache state (none of it changes during the launch): the waves' attention items, and
   // per row its position and whether it is active.
   __shared__ int sblk[DF_WHOLE_CHUNKS * 4];
@@ -1460,10 +1445,15 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     srow[m] = j < off ? len : len + (j - off);
     srow[16 + m] = j < off ? 0 : 1;
   }
-  df_embed_phase(a);
+  tag = (uint32_t)__builtin_amdgcn_readfirstlane(tag_v);
+  if (!df_tag_ok(tag)) {                                   // numbering exhausted: do nothing; the host must clear the workspace
+    if (blockIdx.x == 0 && threadIdx.x == 0) __hip_atomic_fetch_or(a.bar + 64, DEV_ERR_TAGS, __ATOMIC_RELAXED, AG);
+    return;
+  }
+  df_embed_phase(a, tag);
   if (g_q && threadIdx.x < a.rows.M) {                    // the QKV epilogue appends keys and values: block of each row's position
     u64 w = ld_word(a.rowblk + threadIdx.x);
-    for (long spins = 0; (uint32_t)(w >> 32) != a.tag; w = ld_word(a.rowblk + threadIdx.x)) {
+    for (long spins = 0; (uint32_t)(w >> 32) != tag; w = ld_word(a.rowblk + threadIdx.x)) {
       if (++spins > DF_SPIN_LIMIT || ((spins & 63) == 0 && __hip_atomic_load(a.bar + 64, __ATOMIC_RELAXED, AG) != 0)) {
         __hip_atomic_store(a.bar + 64, 1u, __ATOMIC_RELAXED, AG);
         w = 0xFFFFFFFFull;                                 // no block: the row is not appended, every later wait sees the flag
@@ -1480,35 +1470,35 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
     if (g_q) {
       const DArgs& a = df_args();
       const DPhase cur = make_qkv(a, l);
-      if (df_gemm_phase<PE_QKV, SB>(a, cur, lds, srow, &sdead, s0)) return;
+      if (df_gemm_phase<PE_QKV, SB>(a, tag, cur, lds, srow, &sdead, s0)) return;
     }
     if (g_a) {
       const DArgs& a = df_args();
-      if (WHOLE ? df_attn_whole(a, l, aw, lds, sblk, srow, &sdead, s0 + 2) : df_attn_phase(a, l, ait, lds, srow, &sdead, s0 + 2)) return;
+      if (WHOLE ? df_attn_whole(a, tag, l, aw, lds, sblk, srow, &sdead, s0 + 2) : df_attn_phase(a, tag, l, ait, lds, srow, &sdead, s0 + 2)) return;
     }
     if (g_o) {
       const DArgs& a = df_args();
       const DPhase cur = make_o(a, l);
-      if (df_gemm_phase<PE_RESID, SB>(a, cur, lds, srow, &sdead, s0 + 4)) return;
+      if (df_gemm_phase<PE_RESID, SB>(a, tag, cur, lds, srow, &sdead, s0 + 4)) return;
     }
     if (g_g) {
       const DArgs& a = df_args();
       const DPhase cur = make_swiglu(a, l);
       u64* p2 = a.part2 + (size_t)(l & 1) * a.st_part2;
-      if (df_mlp_phase<SB>(a, cur, layer_ptrs(a, l).wdown, p2, df_tag2(a, l), lds, sact, &sdead, s0 + 6)) return;
+      if (df_mlp_phase<SB>(a, tag, cur, layer_ptrs(a, l).wdown, p2, df_tag2(tag, l), lds, sact, &sdead, s0 + 6)) return;
     }
     if (g_r) {
       const DArgs& a = df_args();
       const size_t hi = (size_t)(2 * l + 1);
       const float* gain_next = l + 1 < L ? layer_ptrs(a, l + 1).ln1 : a.final_norm;
-      if (df_reduce_phase(a, l, a.part2 + (size_t)(l & 1) * a.st_part2, df_tag2(a, l), a.h + hi * a.st_h, a.h + (hi + 1) * a.st_h,
+      if (df_reduce_phase(a, tag, l, a.part2 + (size_t)(l & 1) * a.st_part2, df_tag2(tag, l), a.h + hi * a.st_h, a.h + (hi + 1) * a.st_h,
                           a.hg + (hi + 1) * a.st_h, a.sq + (hi + 1) * a.st_sq, gain_next, s_red, lds, &sdead, s0 + 8)) return;
     }
   }
   if (a.with_head && g_l) {
     const DArgs& a = df_args();
     const DPhase cur = make_head(a);
-    df_gemm_phase<PE_LOGITS, SB>(a, cur, lds, srow, &sdead, 2 + L * 10);
+    df_gemm_phase<PE_LOGITS, SB>(a, tag, cur, lds, srow, &sdead, 2 + L * 10);
   }
 }
 

@@ -139,7 +139,9 @@ __device__ __forceinline__ bool grid_barrier(const PArgs& a, uint32_t epoch, int
     int dead = *sdead;
     bool last = false;
     if (threadIdx.x == 0) {
+#ifdef SSD_TRACE
       if (a.trace) a.trace[(size_t)blockIdx.x * 512 + slot] = wall_clock64();
+#endif
       if (!dead) last = __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, AG) == G - 1;
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -164,7 +166,9 @@ __device__ __forceinline__ bool grid_barrier(const PArgs& a, uint32_t epoch, int
         }
         *sdead = dead;
       }
+#ifdef SSD_TRACE
       if (a.trace) a.trace[(size_t)blockIdx.x * 512 + slot + 1] = wall_clock64();
+#endif
     }
   }
   __syncthreads();

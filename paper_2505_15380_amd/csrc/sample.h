@@ -258,6 +258,10 @@ struct AcceptArgs {
   const int32_t* x;      // [B][K]
   const float* uniforms; // [B][K+1] or NULL -> Philox(seed, seq, step, slot)
   uint64_t seed, step;
+  const int32_t* step_dev;  // when set: two words (low, high) of a device-resident cycle counter that is added to `step`, so
+                         // that a captured graph of a cycle draws fresh uniforms at every replay
+  int bump_step;         // the committing thread advances that counter (the last sampling kernel of a cycle without drafts)
+  int bump_launch;       // this kernel follows a forward on a.kv: the committing thread advances the cache's launch number
   int slot_base;         // r_i uses slot slot_base + i - 1, the emitted token slot_base + K
   int B, K, V;
   float beta;
@@ -323,13 +327,16 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
   const float* pt = a.pt + (size_t)b * a.pt_seq_stride;
   const float* pd = a.pd + (size_t)b * K * V;
   const uint32_t seq = (uint32_t)(a.seq0 + b);
+  uint64_t step = a.step;
+  if (a.step_dev) step += (uint64_t)(uint32_t)a.step_dev[0] | ((uint64_t)(uint32_t)a.step_dev[1] << 32);
   // a single sequence commits without waiting for anyone: its cache state is requested now (nothing but this kernel's
   // own commit changes it), so that the commit at the end is stores only
   const bool solo = a.kv.len != nullptr && a.B == 1;
-  int st_len = 0, st_npend = 0, st_owned = 0, st_top = 0, st_err = 0;
+  int st_len = 0, st_npend = 0, st_owned = 0, st_top = 0, st_err = 0, st_launch = 0;
+  uint32_t st_dev_err = 0;
   if (solo && tid == 0) {
     st_len = a.kv.len[seq]; st_npend = a.kv.n_pend[seq]; st_owned = a.kv.owned[seq];
-    st_top = a.kv.ctl[0]; st_err = a.kv.ctl[1];
+    st_top = a.kv.ctl[0]; st_err = a.kv.ctl[1]; st_launch = a.kv.ctl[3]; st_dev_err = *a.kv.err;
   }
 
   if (tid < WAVE) {
@@ -337,7 +344,7 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
     if (tid < K) {
       const int xi = min(max(a.x[b * K + tid], 0), V - 1);
       const float ptx = pt[(size_t)tid * V + xi], pdx = pd[(size_t)tid * V + xi];
-      const float r = a.uniforms ? a.uniforms[b * (K + 1) + tid] : philox_uniform(a.seed, seq, a.step, a.slot_base + tid);
+      const float r = a.uniforms ? a.uniforms[b * (K + 1) + tid] : philox_uniform(a.seed, seq, step, a.slot_base + tid);
       float thr;
       if (pdx > ptx) thr = __fadd_rn(__fdiv_rn(ptx, pdx), a.beta);
       else thr = __fadd_rn(1.0f, a.beta);
@@ -347,7 +354,7 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
     if (tid == 0) sh_n = min(__ffsll((long long)rej) - 1, K);
   }
   if (tid == WAVE)                                         // the uniform of the draw: one thread of the second wave
-    sh_u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, a.step, a.slot_base + K);
+    sh_u = a.uniforms ? a.uniforms[b * (K + 1) + K] : philox_uniform(a.seed, seq, step, a.slot_base + K);
   __syncthreads();
   const int n = sh_n;
   const float u = sh_u;
@@ -400,6 +407,15 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
   if (a.kv.len == nullptr) return;
   if (solo) {                                              // kv_truncate + kv_publish on the values read at the start
     if (tid == 0) {
+      if (a.bump_launch) a.kv.ctl[3] = st_launch + 1;
+      if (a.bump_step && a.step_dev) {
+        const uint64_t nx = step - a.step + 1;
+        ((int32_t*)a.step_dev)[0] = (int32_t)(uint32_t)nx;
+        ((int32_t*)a.step_dev)[1] = (int32_t)(uint32_t)(nx >> 32);
+      }
+      a.kv.mirror[2 * a.kv.max_seqs] = st_err;
+      a.kv.mirror[2 * a.kv.max_seqs + 1] = (int32_t)st_dev_err;
+      if (st_dev_err) return;                              // the forward did not finish: its logits mean nothing, commit nothing
       const int new_len = st_len + st_npend + n;
       const int keep = ceil_div(new_len, a.kv.bt);
       int own = st_owned, top = st_top;
@@ -415,7 +431,6 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
       a.kv.n_pend[seq] = 1;
       a.kv.mirror[2 * seq] = new_len;
       a.kv.mirror[2 * seq + 1] = 1;
-      a.kv.mirror[2 * a.kv.max_seqs] = st_err;
     }
     return;
   }
@@ -428,6 +443,14 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
   __syncthreads();
   if (!sh_last || tid != 0) return;
   __threadfence();
+  a.kv.ctl[2] = 0;
+  if (a.bump_launch) kv_bump_launch(a.kv);
+  if (a.bump_step && a.step_dev) {
+    const uint64_t nx = step - a.step + 1;
+    ((int32_t*)a.step_dev)[0] = (int32_t)(uint32_t)nx;
+    ((int32_t*)a.step_dev)[1] = (int32_t)(uint32_t)(nx >> 32);
+  }
+  if (*a.kv.err) { kv_publish_flags(a.kv); return; }        // the forward did not finish: commit nothing
   for (int s = 0; s < a.B; ++s) {
     const int sq = a.seq0 + s;
     const int nn = a.n_acc ? ((volatile int32_t*)a.n_acc)[s] : 0;
@@ -437,7 +460,6 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
     a.kv.n_pend[sq] = 1;
     kv_publish(a.kv, sq);
   }
-  a.kv.ctl[2] = 0;
 }
 
 template <int SP>
@@ -458,10 +480,16 @@ __global__ void __launch_bounds__(SBLOCK) k_warp_accept(WarpArgs w, AcceptArgs a
 }
 
 // ------------------------------------------------------------------------------------------ small state kernels
-// Truncate one sequence and (optionally) set its pending token from a value or from device memory.
+// Truncate one sequence and (optionally) set its pending token from a value or from device memory.  new_len >= 0 is a
+// rollback: a target beyond the cached length is refused (the state stays, KV_ERR_ROLLBACK is raised).  add_len is
+// the commit of a prefill chunk.  after_forward: the kernel follows a forward on this cache (advances its launch number;
+// commits nothing if that forward did not finish).
 __global__ void k_kv_set(KvView kv, int seq, int new_len, int add_len, int set_pending, int pending_value,
-                         const int32_t* pending_ptr) {
+                         const int32_t* pending_ptr, int after_forward) {
   if (threadIdx.x || blockIdx.x) return;
+  if (after_forward) kv_bump_launch(kv);
+  if (*kv.err) { kv_publish_flags(kv); return; }
+  if (new_len > kv.len[seq]) { kv.ctl[1] |= KV_ERR_ROLLBACK; kv_publish_flags(kv); return; }
   const int target = new_len >= 0 ? new_len : kv.len[seq] + add_len;
   kv_truncate(kv, seq, target);
   if (set_pending) {
@@ -473,8 +501,14 @@ __global__ void k_kv_set(KvView kv, int seq, int new_len, int add_len, int set_p
 
 // Draft cache after a verification of K drafts (see ssd_kv_follow).
 __global__ void k_kv_follow(KvView kv, int n_seqs, int K, const int32_t* n_acc, const int32_t* next_tok,
-                            const int32_t* x) {
+                            const int32_t* x, int32_t* step_dev) {
   if (threadIdx.x || blockIdx.x) return;
+  if (step_dev) {                                          // last kernel of a captured cycle: the next replay is the next step
+    const uint64_t nx = ((uint64_t)(uint32_t)step_dev[0] | ((uint64_t)(uint32_t)step_dev[1] << 32)) + 1;
+    step_dev[0] = (int32_t)(uint32_t)nx;
+    step_dev[1] = (int32_t)(uint32_t)(nx >> 32);
+  }
+  if (*kv.err) { kv_publish_flags(kv); return; }
   for (int s = 0; s < n_seqs; ++s) {
     const int n = n_acc[s];
     if (n < K) {
@@ -498,7 +532,26 @@ __global__ void k_kv_init(KvView kv) {
     kv.mirror[2 * i] = 0; kv.mirror[2 * i + 1] = 0;
   }
   if (i < kv.max_seqs * kv.mbps) kv.table[i] = -1;
-  if (i == 0) { kv.ctl[0] = kv.n_blocks; kv.ctl[1] = 0; kv.ctl[2] = 0; kv.mirror[2 * kv.max_seqs] = 0; }
+  if (i == 0) {
+    kv.ctl[0] = kv.n_blocks; kv.ctl[1] = 0; kv.ctl[2] = 0; kv.ctl[3] = 1; kv.ctl[4] = 0; kv.ctl[5] = 0;
+    kv.mirror[2 * kv.max_seqs] = 0; kv.mirror[2 * kv.max_seqs + 1] = 0;
+  }
+}
+
+// Clears the sticky error state (the caller has re-zeroed the barrier words and the tagged workspace on the same stream)
+// and restarts the launch numbering; sequence state is left as it is.
+__global__ void k_kv_clear_error(KvView kv) {
+  if (threadIdx.x || blockIdx.x) return;
+  kv.ctl[1] = 0; kv.ctl[2] = 0; kv.ctl[3] = 1;
+  *kv.err = 0u;
+  kv_publish_flags(kv);
+}
+
+// Test hook: raise device error bits / set the launch number (see ssd_kv_test_hook).
+__global__ void k_kv_poke(KvView kv, uint32_t err_bits, int launch_no) {
+  if (threadIdx.x || blockIdx.x) return;
+  if (err_bits) *kv.err = *kv.err | err_bits;
+  if (launch_no > 0) kv.ctl[3] = launch_no;
 }
 
 // Rotary table: (cos, sin)(pos * base^(-2i/hd)) evaluated in fp64, rounded once to fp32.

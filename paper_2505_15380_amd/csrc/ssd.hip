@@ -302,7 +302,8 @@ struct ssd_kv {
   unsigned long long* trace;       // [256][512] clock samples of the persistent kernel's barriers
   bool trace_on = false;
   int NP, p_rows;
-  uint32_t epoch = 0;
+  uint32_t bar_epoch = 0;          // grid barriers executed so far by the kernel with barriers (compared wrap-safe)
+  uint32_t launch_no = 1;          // host's copy of ctl[3]: the number the next forward on this cache will read
   int persistent_wgs = 0;          // 0: the persistent kernel is not usable for this cache
   int cus = 0;                     // compute units of the device
   // tagged workspace of the barrier-free forward (see dataflow.h); null when that kernel is not usable
@@ -312,9 +313,8 @@ struct ssd_kv {
   bool attn_whole = false;   // barrier-free kernel: attention of short prefixes without parts.  Default: caches with two
                              // pending slots (draft caches: one-row steps gain 10 %); SSD_ATTN_WHOLE=0 never, 1 every cache
   bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared GEMM kernel (SSD_GEMM=narrow: the generic one)
-  bool narrow_down = false;  // SSD_GEMM=narrow_down: only the down projection on the generic kernel
-  int wide_mtw = 0;          // SSD_WIDE_MTW=1..8: row tiles per workgroup of the LDS-shared kernel (0: chosen per launch)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
+  bool capturing = false;          // a cycle is being captured on this cache: no synchronisation, no fallback kernels
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel, 4 the same with attention without parts
   bool last_whole = false;
   int df_sb = 0;             // SSD_DF_FLIGHT=2|4|10|12: words in flight per thread of the operand staging (0: chosen per launch)
@@ -335,7 +335,7 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   int32_t* owned = cv.take<int32_t>(max_seqs);
   int32_t* table = cv.take<int32_t>((size_t)max_seqs * mbps);
   int32_t* free_stack = cv.take<int32_t>(n_blocks);
-  int32_t* ctl = cv.take<int32_t>(4);
+  int32_t* ctl = cv.take<int32_t>(8);
   int32_t* rpos = cv.take<int32_t>(Mmax);
   int32_t* ract = cv.take<int32_t>(Mmax);
   int32_t* scratch_i = cv.take<int32_t>(2 * max_seqs);
@@ -427,9 +427,10 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   v.pool = dev_pool;
   v.n_blocks = n_blocks; v.bt = block_tokens; v.mbps = mbps; v.max_seqs = max_seqs; v.pcap = pending_cap;
   v.n_layers = m->c.n_layers; v.nkv = m->c.n_kv_heads; v.hd = m->c.head_dim;
-  hipError_t e = hipHostMalloc((void**)&kv->mirror_host, (2 * max_seqs + 1) * sizeof(int32_t), hipHostMallocMapped);
+  v.err = kv->bar + 64;
+  hipError_t e = hipHostMalloc((void**)&kv->mirror_host, (2 * max_seqs + 2) * sizeof(int32_t), hipHostMallocMapped);
   if (e != hipSuccess) { delete kv; return fail(SSD_EHIP, "hipHostMalloc: %s", hipGetErrorString(e)); }
-  memset(kv->mirror_host, 0, (2 * max_seqs + 1) * sizeof(int32_t));
+  memset(kv->mirror_host, 0, (2 * max_seqs + 2) * sizeof(int32_t));
   e = hipHostGetDevicePointer((void**)&v.mirror, kv->mirror_host, 0);
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "hipHostGetDevicePointer: %s", hipGetErrorString(e)); }
   kv->len_ub.assign(max_seqs, 0);
@@ -449,8 +450,7 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 16) {
-      int want = std::max(32, cdiv(m->c.d_ffn / 16, 2));            // two gate/up tile pairs per workgroup
-      if (const char* env = getenv("SSD_PERSISTENT_WGS")) want = atoi(env);
+      const int want = std::max(32, cdiv(m->c.d_ffn / 16, 2));      // two gate/up tile pairs per workgroup
       kv->persistent_wgs = std::max(0, std::min(want, cus));        // one workgroup per CU at most: all co-resident
       kv->cus = cus;
     }
@@ -472,9 +472,6 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
     if (kv->df_sb != 2 && kv->df_sb != 4 && kv->df_sb != 10 && kv->df_sb != 12) kv->df_sb = 0;
     env = getenv("SSD_GEMM");
     kv->gemm_wide = !(env && strcmp(env, "narrow") == 0);
-    kv->narrow_down = env && strcmp(env, "narrow_down") == 0;
-    env = getenv("SSD_WIDE_MTW");
-    kv->wide_mtw = env ? atoi(env) : 0;
   }
   if (e != hipSuccess) { (void)hipHostFree(kv->mirror_host); delete kv; return fail(SSD_EHIP, "k_kv_init: %s", hipGetErrorString(e)); }
   *out = kv;
@@ -488,6 +485,22 @@ extern "C" int ssd_kv_destroy(ssd_kv* kv) {
   return SSD_OK;
 }
 
+// Error words that device code left in the host-mapped mirror (no synchronisation: what has been published so far).
+// They are sticky until ssd_kv_clear_error.
+static int kv_check_flags(const ssd_kv* kv) {
+  const volatile int32_t* mh = kv->mirror_host;
+  const int dev_err = mh[2 * kv->max_seqs + 1], st_err = mh[2 * kv->max_seqs];
+  if (dev_err & (int)DEV_ERR_TIMEOUT)
+    return fail(SSD_EHIP, "a bounded wait inside a persistent forward kernel timed out: results since then are void and "
+                          "nothing was committed; call ssd_kv_clear_error before using this cache again");
+  if (dev_err & (int)DEV_ERR_TAGS)
+    return fail(SSD_EHIP, "the launch numbering of this cache is exhausted; call ssd_kv_clear_error");
+  if (st_err & KV_ERR_ROLLBACK)
+    return fail(SSD_EINVAL, "a rollback asked for more positions than the sequence held and was refused");
+  if (st_err & KV_ERR_POOL) return fail(SSD_ENOMEM, "device allocator reported pool exhaustion");
+  return SSD_OK;
+}
+
 // Bring the host's length bounds up to date with the device (synchronises the stream).
 static int kv_refresh(ssd_kv* kv, hipStream_t st) {
   HIP_TRY(hipStreamSynchronize(st));
@@ -495,8 +508,28 @@ static int kv_refresh(ssd_kv* kv, hipStream_t st) {
     kv->len_ub[s] = kv->mirror_host[2 * s];
     kv->npend_ub[s] = kv->mirror_host[2 * s + 1];
   }
-  if (kv->mirror_host[2 * kv->max_seqs]) return fail(SSD_ENOMEM, "device allocator reported pool exhaustion");
+  return kv_check_flags(kv);
+}
+
+// Re-zero everything the persistent kernels synchronise through and restart the launch numbering (stream-ordered).
+static int kv_clear_sync_state(ssd_kv* kv, hipStream_t st) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  HIP_TRY(hipStreamIsCapturing(st, &cs));
+  if (cs != hipStreamCaptureStatusNone) return fail(SSD_EINVAL, "the cache's launch numbering cannot be cleared inside a stream capture");
+  HIP_TRY(hipMemsetAsync(kv->bar, 0, 128 * sizeof(uint32_t), st));
+  HIP_TRY(hipMemsetAsync(kv->tickets, 0, sizeof(int32_t) * std::max(kv->m->c.d_model / 32 + 1, kv->max_seqs * kv->max_rows * kv->m->c.n_kv_heads), st));
+  if (kv->t_base && kv->t_words) HIP_TRY(hipMemsetAsync(kv->t_base, 0, kv->t_words * sizeof(u64), st));
+  hipLaunchKernelGGL(k_kv_clear_error, dim3(1), dim3(1), 0, st, kv->v);
+  LAUNCH_CHECK();
+  kv->launch_no = 1;
+  kv->bar_epoch = 0;
   return SSD_OK;
+}
+
+// Before enqueuing `n` more forwards on the cache: the launch numbers they will read must stay below the limit.
+static int kv_launch_guard(ssd_kv* kv, hipStream_t st, uint32_t n) {
+  if (kv->launch_no + n < TAG_LIMIT) return SSD_OK;
+  return kv_clear_sync_state(kv, st);
 }
 
 // Can sequences [seq0, seq0+B) each take R more positions?  Uses the host's upper bounds; refreshes once
@@ -658,13 +691,13 @@ static int forward_persistent(const ssd_model* m, ssd_kv* kv, Rows rows, int B, 
   int max_len = 0;
   for (int s = rows.seq0; s < rows.seq0 + B; ++s) max_len = std::max(max_len, kv->len_ub[s]);
   a.n_parts = std::min(kv->NP, cdiv(max_len + rows.R, ATT_PART));
-  a.tickets = kv->tickets; a.bar = kv->bar; a.epoch_base = kv->epoch;
+  a.tickets = kv->tickets; a.bar = kv->bar; a.epoch_base = kv->bar_epoch;
   a.trace = (kv->trace_on && 2 * (1 + 5 * c.n_layers) <= 512) ? kv->trace : nullptr;
   const int G = kv->persistent_wgs, NU = 2 * G, npairs = c.d_model / 32;
   auto splits = [&](int K) { return std::max(1, std::min(std::min(NU / npairs, (K / 32) / 4), P_MAX_SPLITS)); };
   a.gs_o = (c.n_q_heads * c.head_dim) / 32 <= 4 * PF_K ? 1 : splits(c.n_q_heads * c.head_dim);   // <= PF_K k-tiles per wave: all prefetched
   a.gs_d = splits(c.d_ffn);
-  kv->epoch += (with_head ? 1u : 0u) + 5u * (uint32_t)c.n_layers;      // barriers this launch executes
+  kv->bar_epoch += (with_head ? 1u : 0u) + 5u * (uint32_t)c.n_layers;  // barriers this launch executes
   ProfScope ps(PROF_PERSISTENT, st);
   hipLaunchKernelGGL(k_forward_persistent, dim3(G), dim3(PBLOCK), 0, st, a);
   LAUNCH_CHECK();
@@ -718,7 +751,6 @@ static int forward_dataflow(const ssd_model* m, ssd_kv* kv, Rows rows, int B, in
   a.part2 = kv->t_part2; a.st_part2 = (size_t)(c.d_ffn / 32) * PR * c.d_model;
   a.NP = kv->NP; a.n_parts = n_parts; a.g_mlp = g_mlp; a.small_stride = small_stride;
   a.bar = kv->bar;
-  a.tag = ++kv->epoch;
   a.trace = kv->trace_on ? kv->trace : nullptr;
   ProfScope ps(PROF_PERSISTENT, st);
   kv->last_whole = whole;
@@ -744,11 +776,19 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   const int nqd = nq * hd, nqkv = m->n_qkv();
   Rows rows = kv->rows;
   rows.M = M; rows.R = R; rows.seq0 = seq0;
+  {                                     // every forward is followed by a kernel that advances the cache's launch number
+    const int rc = kv_launch_guard(kv, st, 1);
+    if (rc) return rc;
+    ++kv->launch_no;
+  }
+  if (kv->capturing && !(kv->persistent_wgs > 0 && M <= kv->p_rows && kv->dataflow))
+    return fail(SSD_ENOSUP, "this launch does not fit the barrier-free forward kernel: it cannot be captured");
   if (kv->persistent_wgs > 0 && M <= kv->p_rows) {
     if (kv->dataflow) {
       const int rc = forward_dataflow(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
       if (rc >= 0) { kv->last_path = kv->last_whole ? 4 : 3; return rc; }
     }
+    if (kv->capturing) return fail(SSD_ENOSUP, "this launch does not fit the barrier-free forward kernel: it cannot be captured");
     kv->last_path = 2;
     return forward_persistent(m, kv, rows, B, pcap, dev_tokens, tok_stride, with_head, st);
   }
@@ -782,9 +822,9 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   // down projection: slices of the long k range per workgroup, if that still gives half the CUs a workgroup
   // (measured: 18.7 vs 44.6 us per launch on the 1.5B shape at 72 rows, 168 workgroups; 18.7 vs 17.5 us on the 0.5B
   // shape at 112 rows, where it has 80)
-  const bool big = M >= 256 && !kv->wide_mtw;
-  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, kv->wide_mtw, MAX_SPLITS, big);
-  const bool wide_down = wide && !kv->narrow_down &&
+  const bool big = M >= 256;
+  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, 0, MAX_SPLITS, big);
+  const bool wide_down = wide &&
                          2 * down_plan.wa.n_colg * down_plan.wa.n_rowg * down_plan.wa.n_slices >= kv->cus;
   const int gs_d = wide_down ? down_plan.wa.n_slices : splits_for(c.d_ffn);
   int n_part = 0;
@@ -827,7 +867,7 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
       ProfScope ps(PROF_GATEUP, st);
       if (wide) {                                          // many rows: activations shared through LDS (see gemm.h)
         // two row tiles per workgroup: measured best on both shapes (more workgroups beat fewer weight re-reads)
-        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, kv->wide_mtw ? kv->wide_mtw : 2, 1, big), st);
+        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, 2, 1, big), st);
       } else {
         rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st);
       }
@@ -882,8 +922,9 @@ extern "C" int ssd_prefill(ssd_model* m, ssd_kv* kv, int seq, const int32_t* dev
   if (rc) return rc;
   if (!dev_tokens || n < 1) return fail(SSD_EINVAL, "prefill needs at least one token");
   if (seq < 0 || seq >= kv->max_seqs) return fail(SSD_EINVAL, "sequence %d out of range", seq);
+  if ((rc = kv_check_flags(kv))) return rc;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, 0, 0, 0, 0, (const int32_t*)nullptr);
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, 0, 0, 0, 0, (const int32_t*)nullptr, 0);
   LAUNCH_CHECK();
   kv->len_ub[seq] = 0;
   kv->npend_ub[seq] = 0;
@@ -892,11 +933,11 @@ extern "C" int ssd_prefill(ssd_model* m, ssd_kv* kv, int seq, const int32_t* dev
   for (int i = 0; i < n - 1; i += chunk) {
     const int R = std::min(chunk, n - 1 - i);
     if ((rc = forward_any(m, kv, seq, 1, R, 0, dev_tokens + i, 0, false, st))) return rc;
-    hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, R, 0, 0, (const int32_t*)nullptr);
+    hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, R, 0, 0, (const int32_t*)nullptr, 1);
     LAUNCH_CHECK();
     kv->len_ub[seq] += R;
   }
-  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, 0, 1, 0, dev_tokens + (n - 1));
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, -1, 0, 1, 0, dev_tokens + (n - 1), 0);
   LAUNCH_CHECK();
   kv->npend_ub[seq] = 1;
   return SSD_OK;
@@ -904,10 +945,13 @@ extern "C" int ssd_prefill(ssd_model* m, ssd_kv* kv, int seq, const int32_t* dev
 
 // ------------------------------------------------------------------------------------------------ step
 // Forward + warp + acceptance + commit for sequences 0..B-1.
+// `step_dev`: when set, the cycle counter on the device is added to step_ctr (captured cycles); `bump_step`: this
+// step's sampling kernel is the last of its cycle and advances that counter.
 static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, const float* dev_pd,
                 const ssd_sample_config* cfg, uint64_t step_ctr, int slot_base, int32_t* dev_n, int32_t* dev_next,
                 int next_stride, float* probs_out, size_t probs_seq_stride, bool probs_last_row_only,
-                float* logits_out, hipStream_t st) {
+                float* logits_out, hipStream_t st, const int32_t* step_dev = nullptr, bool bump_step = false,
+                bool full_pcap = false) {
   const ssd_model_config& c = m->c;
   // Rows per sequence that carry pending tokens: the cache's capacity, or less when the host knows that no sequence of
   // the launch holds that many (a draft cache owes two tokens only right after a fully accepted cycle; at 16 sequences
@@ -915,9 +959,10 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
   int pcap = 1;
   for (int s = 0; s < B; ++s) pcap = std::max(pcap, kv->npend_ub[s]);
   pcap = std::min(pcap, kv->v.pcap);
+  if (full_pcap) pcap = kv->v.pcap;     // a captured step must hold whatever the sequences owe at any replay
   const int R = pcap + K, M = B * R, V = c.vocab;
   int rc;
-  if ((rc = kv_check_room(kv, 0, B, R, st))) return rc;
+  if (!kv->capturing && (rc = kv_check_room(kv, 0, B, R, st))) return rc;      // (a captured cycle checks before each replay)
   if ((rc = forward_any(m, kv, 0, B, R, pcap, dev_x, K, true, st))) return rc;
   if (logits_out) HIP_TRY(hipMemcpyAsync(logits_out, kv->logits, (size_t)M * V * 4, hipMemcpyDeviceToDevice, st));
 
@@ -946,6 +991,7 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
     LAUNCH_CHECK();
   }
   a.pd = dev_pd; a.x = dev_x; a.uniforms = nullptr; a.seed = cfg->seed; a.step = step_ctr;
+  a.step_dev = step_dev; a.bump_step = bump_step ? 1 : 0; a.bump_launch = 1;
   a.B = B; a.K = K; a.V = V; a.beta = cfg->beta;
   a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
   a.kv = kv->v; a.seq0 = 0;
@@ -974,6 +1020,7 @@ extern "C" int ssd_verify(ssd_model* target, ssd_kv* kv, int n_seqs, const int32
   if (K < 0 || K > SSD_MAX_K || K + 1 > kv->max_rows) return fail(SSD_EINVAL, "K = %d out of range (max_rows %d)", K, kv->max_rows);
   if (K > 0 && (!dev_draft_tokens || !dev_draft_probs)) return fail(SSD_EINVAL, "draft tokens / probabilities are null");
   if (!dev_n_accepted || !dev_next_token) return fail(SSD_EINVAL, "output pointers are null");
+  if ((rc = kv_check_flags(kv))) return rc;
   hipStream_t st = (hipStream_t)stream;
   if (prefix_len) {
     if ((rc = kv_refresh(kv, st))) return rc;
@@ -1000,11 +1047,12 @@ extern "C" int ssd_draft_step(ssd_model* draft, ssd_kv* kv_d, int n_seqs, const 
   if (!dev_token_out || token_stride < 1) return fail(SSD_EINVAL, "token output is null");
   if (dev_probs_out && probs_stride < (size_t)draft->c.vocab) return fail(SSD_EINVAL, "probs_stride < vocab");
   if (kv_d->max_rows < kv_d->v.pcap) return fail(SSD_EINVAL, "cache rows too small");
+  if ((rc = kv_check_flags(kv_d))) return rc;
   hipStream_t st = (hipStream_t)stream;
-  // the token is drawn with the uniform of slot `draft_idx` of this cycle: pass it as the step's only slot
+  // the token is drawn with the uniform of slot SSD_DRAFT_SLOT0 + draft_idx of this cycle: the step's only slot
   ssd_sample_config c2 = *cfg;
   c2.beta = 0.0f;
-  rc = step(draft, kv_d, n_seqs, 0, nullptr, nullptr, &c2, step_ctr, draft_idx, nullptr, dev_token_out, token_stride,
+  rc = step(draft, kv_d, n_seqs, 0, nullptr, nullptr, &c2, step_ctr, SSD_DRAFT_SLOT0 + draft_idx, nullptr, dev_token_out, token_stride,
             dev_probs_out, probs_stride, true, nullptr, st);
   if (rc) return rc;
   for (int s = 0; s < n_seqs; ++s) { kv_d->len_ub[s] += kv_d->npend_ub[s]; kv_d->npend_ub[s] = 1; }
@@ -1015,13 +1063,16 @@ extern "C" int ssd_kv_rollback(ssd_kv* kv, int seq, int new_len, int pending_tok
   if (!kv) return fail(SSD_EINVAL, "null handle");
   if (seq < 0 || seq >= kv->max_seqs) return fail(SSD_EINVAL, "sequence %d out of range", seq);
   hipStream_t st = (hipStream_t)stream;
+  int rc = kv_check_flags(kv);
+  if (rc) return rc;
+  // The host knows an upper bound of the length only; beyond it the request is refused here.  Between the device's length
+  // and that bound the kernel refuses it: the state stays as it is and the next call on this cache reports the error.
   if (new_len < 0 || new_len > kv->len_ub[seq]) {
-    int rc = kv_refresh(kv, st);
-    if (rc) return rc;
+    if ((rc = kv_refresh(kv, st))) return rc;
     if (new_len < 0 || new_len > kv->len_ub[seq])
       return fail(SSD_EINVAL, "rollback to %d but sequence %d holds %d positions", new_len, seq, kv->len_ub[seq]);
   }
-  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, new_len, 0, 1, pending_token, (const int32_t*)nullptr);
+  hipLaunchKernelGGL(k_kv_set, dim3(1), dim3(1), 0, st, kv->v, seq, new_len, 0, 1, pending_token, (const int32_t*)nullptr, 0);
   LAUNCH_CHECK();
   kv->len_ub[seq] = new_len;
   kv->npend_ub[seq] = 1;
@@ -1033,8 +1084,12 @@ extern "C" int ssd_kv_follow(ssd_kv* kv_d, int n_seqs, int K, const int32_t* dev
   if (!kv_d || !dev_n_accepted || !dev_next_token || !dev_draft_tokens) return fail(SSD_EINVAL, "null argument");
   if (kv_d->v.pcap != 2) return fail(SSD_EINVAL, "ssd_kv_follow needs a draft cache (pending_cap 2)");
   if (n_seqs < 1 || n_seqs > kv_d->max_seqs || K < 1 || K > SSD_MAX_K) return fail(SSD_EINVAL, "bad n_seqs / K");
+  {
+    const int rc = kv_check_flags(kv_d);
+    if (rc) return rc;
+  }
   hipLaunchKernelGGL(k_kv_follow, dim3(1), dim3(1), 0, (hipStream_t)stream, kv_d->v, n_seqs, K, dev_n_accepted,
-                     dev_next_token, dev_draft_tokens);
+                     dev_next_token, dev_draft_tokens, (int32_t*)nullptr);
   LAUNCH_CHECK();
   for (int s = 0; s < n_seqs; ++s) kv_d->npend_ub[s] = 2;       // the length can only have shrunk
   return SSD_OK;
@@ -1103,11 +1158,182 @@ extern "C" int ssd_kv_free_stack(ssd_kv* kv, void* stream, int32_t* free_stack, 
   if (n_free) *n_free = ctl[0];
   uint32_t bar_err = 0;
   HIP_TRY(hipMemcpy(&bar_err, kv->bar + 64, 4, hipMemcpyDeviceToHost));
-  if (dev_error_flag) *dev_error_flag = ctl[1] | (bar_err ? 2 : 0);
+  if (dev_error_flag) *dev_error_flag = (ctl[1] & KV_ERR_POOL) | (bar_err ? 2 : 0) | (ctl[1] & KV_ERR_ROLLBACK);
   if (free_stack) {
     if (cap < ctl[0]) return fail(SSD_ENOMEM, "cap %d < %d free blocks", cap, ctl[0]);
     if (ctl[0]) HIP_TRY(hipMemcpy(free_stack, kv->v.free_stack, (size_t)ctl[0] * 4, hipMemcpyDeviceToHost));
   }
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ errors on the device
+extern "C" int ssd_kv_clear_error(ssd_kv* kv, void* stream) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  return kv_clear_sync_state(kv, (hipStream_t)stream);
+}
+
+extern "C" int ssd_kv_test_hook(ssd_kv* kv, int what, long long value, void* stream) {
+  if (!kv) return fail(SSD_EINVAL, "null handle");
+  hipStream_t st = (hipStream_t)stream;
+  if (what == SSD_HOOK_TIMEOUT) {
+    hipLaunchKernelGGL(k_kv_poke, dim3(1), dim3(1), 0, st, kv->v, DEV_ERR_TIMEOUT, 0);
+  } else if (what == SSD_HOOK_LAUNCH_NUMBER) {
+    if (value < 1 || value >= (long long)TAG_LIMIT) return fail(SSD_EINVAL, "launch number out of range");
+    hipLaunchKernelGGL(k_kv_poke, dim3(1), dim3(1), 0, st, kv->v, 0u, (int)value);
+    kv->launch_no = (uint32_t)value;
+  } else if (what == SSD_HOOK_LAUNCH_NUMBER_DEVICE_ONLY) {
+    if (value < 1 || value > (long long)TAG_LIMIT) return fail(SSD_EINVAL, "launch number out of range");
+    hipLaunchKernelGGL(k_kv_poke, dim3(1), dim3(1), 0, st, kv->v, 0u, (int)value);
+  } else {
+    return fail(SSD_EINVAL, "unknown hook %d", what);
+  }
+  LAUNCH_CHECK();
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ captured cycle
+struct ssd_cycle {
+  ssd_model *target, *draft;
+  ssd_kv *kv, *kv_d;
+  int n_seqs, K;
+  ssd_sample_config cfg, dcfg;
+  int32_t* x;
+  float* pd;
+  int32_t *n_acc, *next;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  int cap_len_t = -1, cap_len_d = -1;     // the captured launch shapes hold while every length bound stays at or below these
+  int captures = 0;
+};
+
+static void cycle_drop(ssd_cycle* c) {
+  if (c->exec) (void)hipGraphExecDestroy(c->exec);
+  if (c->graph) (void)hipGraphDestroy(c->graph);
+  c->exec = nullptr; c->graph = nullptr;
+}
+
+// Host bookkeeping of one cycle's calls (the bounds the eager calls would have left).
+static void cycle_advance_bounds(ssd_cycle* c) {
+  for (int s = 0; s < c->n_seqs; ++s) {
+    c->kv_d->len_ub[s] += c->kv_d->npend_ub[s] + (c->K - 1);
+    c->kv_d->npend_ub[s] = 2;
+    c->kv->len_ub[s] += c->K + 1;
+    c->kv->npend_ub[s] = 1;
+  }
+}
+
+static int cycle_capture(ssd_cycle* c, hipStream_t st) {
+  cycle_drop(c);
+  int rc;
+  // exact lengths, room for the replays this capture will serve, numbering that cannot run out inside them
+  if ((rc = kv_refresh(c->kv, st)) || (rc = kv_refresh(c->kv_d, st))) return rc;
+  const int K = c->K, V = c->target->c.vocab;
+  int max_t = 0, max_d = 0;
+  for (int s = 0; s < c->n_seqs; ++s) { max_t = std::max(max_t, c->kv->len_ub[s]); max_d = std::max(max_d, c->kv_d->len_ub[s]); }
+  // launch shapes (attention parts, workgroups) are those of a prefix up to 256 positions longer than today's
+  const int ahead = 256;
+  const int lim_t = std::min(c->target->max_positions, c->kv->v.mbps * c->kv->v.bt) - (K + 1);
+  const int lim_d = std::min(c->draft->max_positions, c->kv_d->v.mbps * c->kv_d->v.bt) - (K + 2);
+  c->cap_len_t = std::min(max_t + ahead, lim_t);
+  c->cap_len_d = std::min(max_d + ahead, lim_d);
+  if (c->cap_len_t < max_t || c->cap_len_d < max_d + K + 1) return fail(SSD_ENOMEM, "no room for another cycle");
+  if ((rc = kv_check_room(c->kv, 0, c->n_seqs, K + 1, st)) || (rc = kv_check_room(c->kv_d, 0, c->n_seqs, K + 1, st))) return rc;
+  std::vector<int> lt = c->kv->len_ub, ld = c->kv_d->len_ub, nt = c->kv->npend_ub, nd = c->kv_d->npend_ub;
+  const uint32_t ln_t = c->kv->launch_no, ln_d = c->kv_d->launch_no;
+  for (int s = 0; s < c->n_seqs; ++s) {
+    c->kv->len_ub[s] = c->cap_len_t; c->kv_d->len_ub[s] = c->cap_len_d;
+    c->kv->npend_ub[s] = 1; c->kv_d->npend_ub[s] = 2;      // the first draft step of a cycle may owe two tokens
+  }
+  c->kv->capturing = c->kv_d->capturing = true;
+  auto restore = [&]() { c->kv->len_ub = lt; c->kv_d->len_ub = ld; c->kv->npend_ub = nt; c->kv_d->npend_ub = nd;
+                         c->kv->launch_no = ln_t; c->kv_d->launch_no = ln_d; c->kv->capturing = c->kv_d->capturing = false; };
+  hipError_t e = hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal);
+  if (e != hipSuccess) { restore(); return fail(SSD_EHIP, "hipStreamBeginCapture: %s", hipGetErrorString(e)); }
+  const int32_t* step_dev = c->kv->v.ctl + 4;
+  ssd_sample_config dc = c->dcfg;
+  dc.beta = 0.0f;
+  rc = SSD_OK;
+  for (int i = 0; i < K && !rc; ++i) {
+    rc = step(c->draft, c->kv_d, c->n_seqs, 0, nullptr, nullptr, &dc, 0, SSD_DRAFT_SLOT0 + i, nullptr, c->x + i, K,
+              c->pd + (size_t)i * V, (size_t)K * V, true, nullptr, st, step_dev, false, i == 0);
+    for (int s = 0; s < c->n_seqs; ++s) c->kv_d->npend_ub[s] = 1;        // after a draft step exactly one token is pending
+  }
+  if (!rc) rc = step(c->target, c->kv, c->n_seqs, K, c->x, c->pd, &c->cfg, 0, 0, c->n_acc, c->next, 1, nullptr, 0, false,
+                     nullptr, st, step_dev, false, true);
+  if (!rc) {
+    hipLaunchKernelGGL(k_kv_follow, dim3(1), dim3(1), 0, st, c->kv_d->v, c->n_seqs, K, c->n_acc, c->next, c->x,
+                       c->kv->v.ctl + 4);
+    if (hipGetLastError() != hipSuccess) rc = fail(SSD_EHIP, "k_kv_follow launch failed");
+  }
+  hipGraph_t g = nullptr;
+  e = hipStreamEndCapture(st, &g);
+  restore();
+  if (rc) { if (g) (void)hipGraphDestroy(g); return rc; }
+  if (e != hipSuccess) return fail(SSD_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+  c->graph = g;
+  e = hipGraphInstantiate(&c->exec, g, nullptr, nullptr, 0);
+  if (e != hipSuccess) { cycle_drop(c); return fail(SSD_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+  ++c->captures;
+  return SSD_OK;
+}
+
+extern "C" int ssd_cycle_create(ssd_model* target, ssd_kv* kv, ssd_model* draft, ssd_kv* kv_d, int n_seqs, int K,
+                                const ssd_sample_config* cfg, const ssd_sample_config* dcfg, int32_t* dev_draft_tokens,
+                                float* dev_draft_probs, int32_t* dev_n_accepted, int32_t* dev_next_token,
+                                uint64_t first_step, void* stream, ssd_cycle** out) {
+  int rc = check_pair(target, kv);
+  if (rc || (rc = check_pair(draft, kv_d)) || (rc = check_sample(cfg)) || (rc = check_sample(dcfg))) return rc;
+  if (!out || !dev_draft_tokens || !dev_draft_probs || !dev_n_accepted || !dev_next_token) return fail(SSD_EINVAL, "null argument");
+  if (kv->v.pcap != 1 || kv_d->v.pcap != 2) return fail(SSD_EINVAL, "needs a target cache (pending_cap 1) and a draft cache (pending_cap 2)");
+  if (n_seqs < 1 || n_seqs > kv->max_seqs || n_seqs > kv_d->max_seqs) return fail(SSD_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (K < 1 || K > SSD_MAX_K || K + 1 > kv->max_rows || kv_d->max_rows < 2) return fail(SSD_EINVAL, "K = %d out of range", K);
+  if (target->c.vocab != draft->c.vocab) return fail(SSD_EINVAL, "target and draft vocabularies differ");
+  if (!kv->dataflow || !kv_d->dataflow) return fail(SSD_ENOSUP, "a cycle can be captured only on the barrier-free forward kernel");
+  ssd_cycle* c = new (std::nothrow) ssd_cycle();
+  if (!c) return fail(SSD_ENOMEM, "host allocation failed");
+  c->target = target; c->draft = draft; c->kv = kv; c->kv_d = kv_d; c->n_seqs = n_seqs; c->K = K;
+  c->cfg = *cfg; c->dcfg = *dcfg; c->x = dev_draft_tokens; c->pd = dev_draft_probs; c->n_acc = dev_n_accepted;
+  c->next = dev_next_token;
+  const int32_t words[2] = {(int32_t)(uint32_t)first_step, (int32_t)(uint32_t)(first_step >> 32)};
+  hipError_t e = hipMemcpyAsync(kv->v.ctl + 4, words, sizeof words, hipMemcpyHostToDevice, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);       // `words` is on this stack frame
+  if (e != hipSuccess) { delete c; return fail(SSD_EHIP, "cycle counter: %s", hipGetErrorString(e)); }
+  *out = c;
+  return SSD_OK;
+}
+
+extern "C" int ssd_cycle_launch(ssd_cycle* c, void* stream) {
+  if (!c) return fail(SSD_EINVAL, "null handle");
+  if (!stream) return fail(SSD_EINVAL, "a cycle cannot be captured on the default (NULL) stream: pass a stream of its own");
+  hipStream_t st = (hipStream_t)stream;
+  int rc;
+  if ((rc = kv_check_flags(c->kv)) || (rc = kv_check_flags(c->kv_d))) return rc;
+  const int K = c->K;
+  if ((rc = kv_launch_guard(c->kv, st, 1)) || (rc = kv_launch_guard(c->kv_d, st, (uint32_t)K))) return rc;
+  bool fits = c->exec != nullptr;
+  for (int s = 0; s < c->n_seqs && fits; ++s)
+    fits = c->kv->len_ub[s] <= c->cap_len_t && c->kv_d->len_ub[s] + K + 1 <= c->cap_len_d;
+  if (fits) {                                              // pool room for this cycle, from the bounds alone
+    long bt = 0, bd = 0;
+    for (int s = 0; s < c->kv->max_seqs; ++s) bt += cdiv(c->kv->len_ub[s] + (s < c->n_seqs ? K + 1 : 0), c->kv->v.bt);
+    for (int s = 0; s < c->kv_d->max_seqs; ++s) bd += cdiv(c->kv_d->len_ub[s] + (s < c->n_seqs ? K + 1 : 0), c->kv_d->v.bt);
+    fits = bt <= c->kv->v.n_blocks && bd <= c->kv_d->v.n_blocks;
+  }
+  if (!fits && (rc = cycle_capture(c, st))) return rc;
+  HIP_TRY(hipGraphLaunch(c->exec, st));
+  c->kv->launch_no += 1;
+  c->kv_d->launch_no += (uint32_t)K;
+  c->kv->last_path = 3;
+  cycle_advance_bounds(c);
+  return SSD_OK;
+}
+
+extern "C" int ssd_cycle_captures(const ssd_cycle* c) { return c ? c->captures : 0; }
+
+extern "C" int ssd_cycle_destroy(ssd_cycle* c) {
+  if (!c) return SSD_OK;
+  cycle_drop(c);
+  delete c;
   return SSD_OK;
 }
 
@@ -1117,6 +1343,10 @@ extern "C" int ssd_kv_last_forward_path(const ssd_kv* kv) { return kv ? kv->last
 extern "C" int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned long long* out, int cap, int* n_wgs,
                                   int* n_samples) {
   if (!kv) return fail(SSD_EINVAL, "null handle");
+#ifndef SSD_TRACE
+  (void)enable; (void)stream; (void)out; (void)cap; (void)n_wgs; (void)n_samples;
+  return fail(SSD_ENOSUP, "this build records no phase trace (build with -DSSD_TRACE)");
+#else
   if (out) {
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     const int G = kv->persistent_wgs > 0 ? (kv->dataflow ? std::min(kv->cus, 256) : kv->persistent_wgs) : 0, S = 2 * (1 + 5 * kv->m->c.n_layers);
@@ -1128,4 +1358,5 @@ extern "C" int ssd_trace_barriers(ssd_kv* kv, int enable, void* stream, unsigned
   }
   kv->trace_on = enable != 0;
   return SSD_OK;
+#endif
 }

@@ -44,6 +44,12 @@ class SSDSession:
             B.ssd_kv_follow(self.kv_d, n, K, out["n_accepted"], out["next_token"], self.x)
         return out
 
+    def graph_cycle(self, first_step=0):
+        """The same cycle captured once as a graph (ssd_cycle_create); each launch() of the result replays it with the
+        next cycle index.  Results land in self.x, self.pd, self.n_acc, self.next."""
+        return B.Cycle(self.target, self.kv, self.draft, self.kv_d, self.n_seqs, self.K, self.cfg, self.dcfg, self.x, self.pd,
+                       self.n_acc, self.next, first_step)
+
     def ar_step(self, step, out=None):
         """Plain autoregressive decoding of the target: a verification with no draft tokens."""
         if out is None:

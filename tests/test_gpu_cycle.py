@@ -58,6 +58,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
     V = ts["vocab"]
     seen_full = seen_reject = False
     draft_paths = set()
+    ns = []
     for step in range(steps):
         # alternate a flat and a sharp temperature so that full acceptance and rejection both occur
         # (a temperature of 0.05 multiplies the logits' error by 20: only where the tolerance has that room)
@@ -76,7 +77,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
             dc.length += len(dpend)
             ref = warp_probs(lg[-1:], dcfg["temperature"])[0]
             assert np.abs(gpd[i] - ref).max() <= tol, (step, i)
-            tok = sample_canonical(gpd[i], uniform24(dcfg["seed"], 0, step, i))
+            tok = sample_canonical(gpd[i], OS.draft_uniform(dcfg["seed"], 0, step, i))
             assert tok == int(gx[i]), (step, i)
             dpend = [tok]
         r, u = OS.verify_uniforms(cfg["seed"], 0, step, K)
@@ -86,6 +87,7 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
         assert np.abs(gp - res["pt"]).max() <= tol
         assert (int(out["n_accepted"][0]), int(out["next_token"][0])) == (res["n"], res["next"])
         n, pending = res["n"], res["next"]
+        ns.append(n)
         if n < K:
             dc.length = L + 1 + n; dpend = [pending]; seen_reject = True
         else:
@@ -93,8 +95,9 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
         st, sd = sess.kv.state(0), sess.kv_d.state(0)
         assert st["len"] == tc.length and st["pending"] == [pending]
         assert sd["len"] == dc.length and sd["pending"] == dpend
-    assert (seen_reject and seen_full) or not require_both
+    assert (seen_reject and seen_full) or not require_both, ns
     sess.draft_paths_seen = draft_paths
+    sess.accepted_seen = ns
     return sess
 
 
@@ -211,7 +214,7 @@ def test_batched_cycles_in_lockstep_with_oracle(B, K, target_path):
                 dc[b].length += len(dpend[b])
                 ref = warp_probs(lg[-1:], dcfg["temperature"])[0]
                 assert np.abs(gpd[b, i] - ref).max() <= tol, (step, b, i)
-                tok = sample_canonical(gpd[b, i], uniform24(dcfg["seed"], b, step, i))
+                tok = sample_canonical(gpd[b, i], OS.draft_uniform(dcfg["seed"], b, step, i))
                 assert tok == int(gx[b, i]), (step, b, i)
                 dpend[b] = [tok]
             r, u = OS.verify_uniforms(cfg["seed"], b, step, K)
@@ -395,3 +398,47 @@ def test_errors_are_reported_not_faulted():
                        torch.full((2, 7, V), 1.0 / V, dtype=torch.float32, device="cuda"), 7, cfg, 0)          # n_seqs > max_seqs
     with pytest.raises(ssd.SSDError):                           # more than 512 rows per forward
         ssd.KVCache(pair.gmodel, 33, 16, 40, 16, 4, 1)
+
+
+@pytest.mark.parametrize("workload,K,cycles", [("mini", 3, 80), ("tiny", 2, 0)])
+def test_captured_cycle_replays_like_the_eager_cycle(workload, K, cycles):
+    """One SSD cycle captured as a graph (ssd_cycle_create) and replayed: every replay must leave what the same cycle
+    enqueued call by call leaves on a second, identical session - draft tokens, draft rows, accepted count, emitted
+    token, both caches' lengths - bit for bit, over enough cycles that the graph is captured again for longer prefixes
+    (shapes are captured 256 positions ahead).  The eager cycle is the one the lockstep tests hold against the oracle."""
+    import paper_2505_15380_amd as ssd
+    side = torch.cuda.Stream()                             # HIP cannot capture the default stream
+    if cycles == 0:                                        # fp32 storage runs one launch per operator: no capture
+        sess, _ = make_session(workload, K, beta=0.2, steps=4)
+        torch.cuda.synchronize()
+        with pytest.raises(ssd.SSDError) as e:
+            sess.graph_cycle()
+        assert e.value.code == -4
+        return
+    a, _ = make_session(workload, K, beta=0.3, steps=cycles + 2, n_prefix=200)
+    b, _ = make_session(workload, K, beta=0.3, steps=cycles + 2, n_prefix=200)
+    a.cfg = b.cfg = ssd.sample_config(beta=0.3, seed=77)
+    a.dcfg = b.dcfg = ssd.sample_config(seed=77)           # one seed for both models: the slots keep them apart
+    torch.cuda.synchronize()
+    g = a.graph_cycle(first_step=5)
+    with pytest.raises(ssd.SSDError):
+        g.launch()                                         # on the default stream: refused
+    ns = []
+    with torch.cuda.stream(side):
+        for c in range(cycles):
+            g.launch()
+            b.cycle(5 + c)
+            side.synchronize()
+            assert torch.equal(a.x, b.x), c
+            assert torch.equal(a.pd, b.pd), c
+            assert int(a.n_acc[0]) == int(b.n_acc[0]) and int(a.next[0]) == int(b.next[0]), c
+            ns.append(int(a.n_acc[0]))
+            if c % 16 == 0:                                # eager work on the captured caches between replays
+                sa, sb = a.kv.state(0), b.kv.state(0)
+                assert sa["len"] == sb["len"] and sa["pending"] == sb["pending"]
+                da, db = a.kv_d.state(0), b.kv_d.state(0)
+                assert da["len"] == db["len"] and da["pending"] == db["pending"]
+        assert g.captures() >= 2 and len(set(ns)) > 1
+        assert a.kv.state(0)["table"] == b.kv.state(0)["table"]
+        assert a.kv.free_stack() == b.kv.free_stack()
+    torch.cuda.synchronize()

@@ -98,3 +98,30 @@ def test_allocator_model():
     b = PagedAllocator(n_blocks=4, block_tokens=16, max_seqs=1, max_blocks_per_seq=8)
     with pytest.raises(MemoryError):
         b.reserve(0, 16 * 5)
+
+
+def _first_token_law(draft_slot0, seed=2024, cycles=40000):
+    """Empirical law of the first token a cycle emits when draft and target use ONE seed: x ~ pd drawn with the
+    uniform of slot draft_slot0, then Eq. 5-6 with the verification's slots 0 (r_1) and 1 (the emitted token)."""
+    from oracle.accept import accept_canonical, sample_canonical
+    from oracle.philox import uniform24
+    pd = np.array([[0.55, 0.25, 0.15, 0.05]], np.float32)
+    pt = np.array([[0.10, 0.30, 0.20, 0.40], [0.25, 0.25, 0.25, 0.25]], np.float32)
+    counts = np.zeros(4)
+    for step in range(cycles):
+        x = sample_canonical(pd[0], uniform24(seed, 0, step, draft_slot0))
+        r, u = S.verify_uniforms(seed, 0, step, 1)
+        n, nxt, _ = accept_canonical(pt, pd, [x], r, u, 0.0)
+        counts[x if n == 1 else nxt] += 1
+    return counts / cycles, pt[0].astype(np.float64)
+
+
+def test_one_seed_for_draft_and_target_keeps_the_target_law():
+    """Alg. 1 draws r_i afresh: with the draft's draws on slots of their own (oracle.ssd.DRAFT_SLOT0), a caller who
+    gives both models the same seed still emits the target's law at beta = 0.  The mistake this guards against -
+    drawing x_1 with the uniform that Eq. 5 then compares, i.e. slot 0 - couples the two and visibly bends the law."""
+    law, pt = _first_token_law(S.DRAFT_SLOT0)
+    assert np.abs(law - pt).max() < 0.01                    # 40000 cycles: three sigma is 0.0075
+    assert S.draft_uniform(5, 1, 2, 3) != S.verify_uniforms(5, 1, 2, 4)[0][3]
+    bent, _ = _first_token_law(0)                           # the planted mistake
+    assert np.abs(bent - pt).max() > 0.05
