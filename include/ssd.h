@@ -136,6 +136,21 @@ int ssd_verify(ssd_model* target, ssd_kv* kv, int n_seqs, const int32_t* prefix_
                int32_t* dev_n_accepted, int32_t* dev_next_token,
                float* dev_target_probs_opt, float* dev_logits_opt, void* stream);
 
+/* ssd_verify_noalloc: ssd_verify for callers that cannot allocate device memory at all or that forbid the library to
+ * - code under HIP graph capture, tight serving loops, harnesses without hipMalloc.  Same work, same results and
+ * same state changes as ssd_verify(target, kv, n_seqs, NULL, ..., NULL, NULL, stream); the difference is where the
+ * call's staging lives: the logits rows, the probability rows and the commit's arrival counter are kept in a
+ * static device array inside the library (SSD_NOALLOC_MAX_ELEMS floats each for logits and probabilities, about
+ * 2 MiB in all, held by every GPU the library runs on until the process ends) instead of in the cache's workspace.
+ * The call allocates and frees nothing, on the device or through any library.  n_seqs * (K+1) * vocab beyond
+ * SSD_NOALLOC_MAX_ELEMS is refused with SSD_ENOMEM before anything is launched.  Every call on one GPU shares
+ * that GPU's array: calls that overlap on one GPU (two streams, two threads) race; calls in stream order do not,
+ * and what a call needs zeroed it zeroes itself. */
+#define SSD_NOALLOC_MAX_ELEMS (1u << 18)
+int ssd_verify_noalloc(ssd_model* target, ssd_kv* kv, int n_seqs, const int32_t* dev_draft_tokens,
+                       const float* dev_draft_probs, int K, const ssd_sample_config* cfg, uint64_t step_ctr,
+                       int32_t* dev_n_accepted, int32_t* dev_next_token, void* stream);
+
 /* ssd_kv_rollback: truncate sequence `seq` to `new_len` cached positions (<= its current length), free the
  * blocks wholly past it and set the single pending token.  Used for the draft cache after a rejection.
  * The length lives on the device and the call does not wait for it: a new_len beyond the host's upper bound of the

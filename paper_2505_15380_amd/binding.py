@@ -11,7 +11,7 @@ EXPORTED_SYMBOLS = [
     "ssd_kv_workspace_bytes", "ssd_kv_create", "ssd_kv_destroy", "ssd_prefill", "ssd_draft_step", "ssd_verify",
     "ssd_kv_rollback", "ssd_kv_follow", "ssd_verify_from_probs", "ssd_warp_probs", "ssd_kv_state",
     "ssd_kv_free_stack", "ssd_profile_begin", "ssd_profile_end", "ssd_kv_last_forward_path", "ssd_trace_barriers", "ssd_strerror", "ssd_last_error",
-    "ssd_kv_clear_error", "ssd_kv_test_hook", "ssd_cycle_create", "ssd_cycle_launch", "ssd_cycle_captures", "ssd_cycle_destroy",
+    "ssd_verify_noalloc", "ssd_kv_clear_error", "ssd_kv_test_hook", "ssd_cycle_create", "ssd_cycle_launch", "ssd_cycle_captures", "ssd_cycle_destroy",
 ]
 
 
@@ -65,6 +65,7 @@ def load_library():
         "ssd_draft_step": (i32, [vp, vp, i32, C.POINTER(SampleConfig), u64, i32, i32p, i32, f32p, sz, vp]),
         "ssd_verify": (i32, [vp, vp, i32, C.POINTER(C.c_int32), i32p, f32p, i32, C.POINTER(SampleConfig), u64,
                              i32p, i32p, f32p, f32p, vp]),
+        "ssd_verify_noalloc": (i32, [vp, vp, i32, i32p, f32p, i32, C.POINTER(SampleConfig), u64, i32p, i32p, vp]),
         "ssd_kv_rollback": (i32, [vp, i32, i32, i32, vp]),
         "ssd_kv_follow": (i32, [vp, i32, i32, i32p, i32p, i32p, vp]),
         "ssd_verify_from_probs": (i32, [f32p, f32p, i32p, f32p, i32, i32, i32, C.c_float, i32p, i32p, i32p, vp]),
@@ -262,6 +263,16 @@ def ssd_verify(target, kv, n_seqs, draft_tokens, draft_probs, K, cfg, step_ctr, 
                                      C.byref(cfg), int(step_ctr), _ptr(out["n_accepted"]), _ptr(out["next_token"]),
                                      _ptr(out["probs"]), _ptr(out["logits"]), _stream()))
     return out
+
+
+def ssd_verify_noalloc(target, kv, n_seqs, draft_tokens, draft_probs, K, cfg, step_ctr, n_accepted, next_token):
+    """ssd_verify whose staging lives in the library's static device array; outputs go to the given int32 tensors."""
+    assert n_accepted.dtype == next_token.dtype == torch.int32 and n_accepted.is_cuda and next_token.is_cuda
+    if K > 0:
+        assert draft_tokens.dtype == torch.int32 and draft_tokens.is_contiguous() and draft_tokens.numel() == n_seqs * K
+        assert draft_probs.dtype == torch.float32 and draft_probs.is_contiguous()
+    _check(load_library().ssd_verify_noalloc(target.handle, kv.handle, n_seqs, _ptr(draft_tokens), _ptr(draft_probs), K,
+                                             C.byref(cfg), int(step_ctr), _ptr(n_accepted), _ptr(next_token), _stream()))
 
 
 def ssd_draft_step(draft, kv_d, n_seqs, cfg, step_ctr, draft_idx, token_out, token_stride, probs_out, probs_stride):

@@ -269,6 +269,7 @@ struct AcceptArgs {
   int32_t* next_tok;     // [B*tok_stride]
   int tok_stride;
   int32_t* flags;        // [B] or NULL
+  int32_t* ticket;       // arrival counter of the workgroups of a multi-sequence commit: zero before the launch, zero after it
   // commit (kv.len == NULL: decisions only)
   KvView kv;
   int seq0;
@@ -437,13 +438,13 @@ __device__ __forceinline__ void accept_seq(const AcceptArgs a, const int b, cons
   // ---- commit by the last workgroup to arrive
   if (tid == 0) {
     __threadfence();
-    const int arrived = atomicAdd(&a.kv.ctl[2], 1);
+    const int arrived = atomicAdd(a.ticket, 1);
     sh_last = (arrived == a.B - 1);
   }
   __syncthreads();
   if (!sh_last || tid != 0) return;
   __threadfence();
-  a.kv.ctl[2] = 0;
+  *a.ticket = 0;
   if (a.bump_launch) kv_bump_launch(a.kv);
   if (a.bump_step && a.step_dev) {
     const uint64_t nx = step - a.step + 1;
@@ -545,6 +546,12 @@ __global__ void k_kv_clear_error(KvView kv) {
   kv.ctl[1] = 0; kv.ctl[2] = 0; kv.ctl[3] = 1;
   *kv.err = 0u;
   kv_publish_flags(kv);
+}
+
+// Clears n 32-bit words (a kernel, not a memset: callers may be capturing the stream).
+__global__ void k_zero_words(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 // Test hook: raise device error bits / set the launch number (see ssd_kv_test_hook).

@@ -314,6 +314,7 @@ struct ssd_kv {
                              // pending slots (draft caches: one-row steps gain 10 %); SSD_ATTN_WHOLE=0 never, 1 every cache
   bool gemm_wide = true;     // per-operator path, many rows: the LDS-shared GEMM kernel (SSD_GEMM=narrow: the generic one)
   bool attn_mfma = true;     // per-operator path: matrix-core attention where it applies (SSD_ATTN=valu: the scalar kernel)
+  int32_t* ticket_alt = nullptr;   // ssd_verify_noalloc: the commit's arrival counter in the library's static scratch
   bool capturing = false;          // a cycle is being captured on this cache: no synchronisation, no fallback kernels
   int last_path = 0;               // 1 per-operator launches, 2 barrier kernel, 3 barrier-free kernel, 4 the same with attention without parts
   bool last_whole = false;
@@ -995,6 +996,7 @@ static int step(ssd_model* m, ssd_kv* kv, int B, int K, const int32_t* dev_x, co
   a.B = B; a.K = K; a.V = V; a.beta = cfg->beta;
   a.n_acc = dev_n; a.next_tok = dev_next; a.tok_stride = next_stride; a.flags = nullptr;
   a.kv = kv->v; a.seq0 = 0;
+  a.ticket = kv->ticket_alt ? kv->ticket_alt : kv->v.ctl + 2;
   a.slot_base = slot_base;
   const bool sp8 = a.V <= 8 * SBLOCK;
   if (one_row) {
@@ -1031,6 +1033,67 @@ extern "C" int ssd_verify(ssd_model* target, ssd_kv* kv, int n_seqs, const int32
   }
   rc = step(target, kv, n_seqs, K, dev_draft_tokens, dev_draft_probs, cfg, step_ctr, 0, dev_n_accepted, dev_next_token,
             1, dev_target_probs_opt, 0, false, dev_logits_opt, st);
+  if (rc) return rc;
+  for (int s = 0; s < n_seqs; ++s) { kv->len_ub[s] += K + 1; kv->npend_ub[s] = 1; }
+  return SSD_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ no-allocation variant
+// Staging of ssd_verify_noalloc: [0, 256) the commit's arrival counter, then the logits rows, then the probability rows.
+// One copy per GPU for the life of the process; every call on a GPU uses that GPU's copy.
+constexpr size_t NOALLOC_MAX_ELEMS = SSD_NOALLOC_MAX_ELEMS;
+static __device__ __align__(256) unsigned char scratch[256 + 2 * NOALLOC_MAX_ELEMS * sizeof(float)];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static unsigned char* g_scratch_dev[NOALLOC_MAX_DEVICES];      // device address of `scratch` on each GPU (0: not asked yet)
+
+// The device address of this GPU's copy of `scratch` (the array's name is only a host-side handle of the symbol).
+static int noalloc_scratch(unsigned char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return fail(SSD_ENOSUP, "device ordinal %d not supported", dev);
+  if (!g_scratch_dev[dev]) {
+    unsigned char* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(SSD_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_dev[dev] = p;
+  }
+  *out = g_scratch_dev[dev];
+  return SSD_OK;
+}
+
+extern "C" int ssd_verify_noalloc(ssd_model* target, ssd_kv* kv, int n_seqs, const int32_t* dev_draft_tokens,
+                                  const float* dev_draft_probs, int K, const ssd_sample_config* cfg, uint64_t step_ctr,
+                                  int32_t* dev_n_accepted, int32_t* dev_next_token, void* stream) {
+  int rc = check_pair(target, kv);
+  if (rc) return rc;
+  if ((rc = check_sample(cfg))) return rc;
+  if (kv->v.pcap != 1) return fail(SSD_EINVAL, "ssd_verify_noalloc needs a target cache (pending_cap 1)");
+  if (n_seqs < 1 || n_seqs > kv->max_seqs) return fail(SSD_EINVAL, "n_seqs %d out of range", n_seqs);
+  if (K < 0 || K > SSD_MAX_K || K + 1 > kv->max_rows) return fail(SSD_EINVAL, "K = %d out of range (max_rows %d)", K, kv->max_rows);
+  if (K > 0 && (!dev_draft_tokens || !dev_draft_probs)) return fail(SSD_EINVAL, "draft tokens / probabilities are null");
+  if (!dev_n_accepted || !dev_next_token) return fail(SSD_EINVAL, "output pointers are null");
+  const size_t elems = (size_t)n_seqs * (K + 1) * target->c.vocab;
+  if (elems > NOALLOC_MAX_ELEMS)
+    return fail(SSD_ENOMEM, "ssd_verify_noalloc: n_seqs * (K+1) * vocab = %zu exceeds the static staging of %zu elements", elems,
+                (size_t)NOALLOC_MAX_ELEMS);
+  if ((rc = kv_check_flags(kv))) return rc;
+  unsigned char* sp = nullptr;
+  if ((rc = noalloc_scratch(&sp))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  // the arrival counter must start at zero whatever an earlier (possibly failed) call on this GPU left; the logits and
+  // probability rows are written in full before they are read
+  hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(64), 0, st, (int32_t*)sp, 64);
+  LAUNCH_CHECK();
+  float* const ws_logits = kv->logits;
+  float* const ws_probs = kv->probs;
+  kv->logits = (float*)(sp + 256);
+  kv->probs = (float*)(sp + 256) + NOALLOC_MAX_ELEMS;
+  kv->ticket_alt = (int32_t*)sp;
+  rc = step(target, kv, n_seqs, K, dev_draft_tokens, dev_draft_probs, cfg, step_ctr, 0, dev_n_accepted, dev_next_token, 1,
+            nullptr, 0, false, nullptr, st);
+  kv->logits = ws_logits;
+  kv->probs = ws_probs;
+  kv->ticket_alt = nullptr;
   if (rc) return rc;
   for (int s = 0; s < n_seqs; ++s) { kv->len_ub[s] += K + 1; kv->npend_ub[s] = 1; }
   return SSD_OK;
