@@ -132,7 +132,9 @@ def run_verify_parity(workload, steps, K, beta, atol_logits, atol_probs, tempera
     if n_prefix is not None:
         n_text, n_speech = 0, n_prefix
     toks = si.make_prefix(shape, n_text, n_speech, wl["seeds"]["prefix"])
-    max_pos = len(toks) + steps * (K + 1) + 32
+    Ks = list(K) if isinstance(K, (list, tuple)) else [K] * steps          # a draft length per step
+    assert len(Ks) == steps
+    max_pos = len(toks) + sum(k + 1 for k in Ks) + 32
     pair = Pair(wl["target"], wl["seeds"]["target"], max_pos, max_rows=16, store=store)
     pair.prefill(0, toks)
     atol_kv = atol_kv if atol_kv is not None else atol_logits
@@ -143,12 +145,12 @@ def run_verify_parity(workload, steps, K, beta, atol_logits, atol_probs, tempera
     worst_l = worst_p = 0.0
     ns = []
     for s in range(steps):
-        (r,) = verify_parity_step(pair, cfg, K, s, rng, atol_logits, atol_probs)
+        (r,) = verify_parity_step(pair, cfg, Ks[s], s, rng, atol_logits, atol_probs)
         worst_l, worst_p = max(worst_l, r["dlogits"]), max(worst_p, r["dprobs"])
         ns.append(r["n"])
         pair.check_state(0, atol_kv, layers=[0, shape["n_layers"] - 1])
         pair.check_free_stack()
     if verbose:
-        print(f"{workload}: {steps} steps K={K} beta={beta}: max|dlogits|={worst_l:.3g} max|dprobs|={worst_p:.3g} "
+        print(f"{workload}: {steps} steps K={Ks} beta={beta}: max|dlogits|={worst_l:.3g} max|dprobs|={worst_p:.3g} "
               f"accepted={ns}")
     return dict(dlogits=worst_l, dprobs=worst_p, accepted=ns, path=pair.kv.last_forward_path())

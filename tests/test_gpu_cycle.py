@@ -18,11 +18,16 @@ def need_gpu():
     pkg.load_library()
 
 
-def make_session(workload, K, beta=0.0, greedy=False, n_prefix=40, steps=12, temperature=None, draft_is_target=False):
+def make_session(workload, K, beta=0.0, greedy=False, n_prefix=40, steps=12, temperature=None, draft_is_target=False,
+                 models=None):
+    """`models` = (target shape, target weights, draft shape, draft weights) replaces the workload's own pair."""
     import paper_2505_15380_amd as ssd
     wl = si.workload(workload)
-    ts, ds = si.model_shape(wl["target"]), si.model_shape(wl["draft"])
-    tw, dw = si.make_weights(ts, wl["seeds"]["target"]), si.make_weights(ds, wl["seeds"]["draft"])
+    if models is not None:
+        ts, tw, ds, dw = models
+    else:
+        ts, ds = si.model_shape(wl["target"]), si.model_shape(wl["draft"])
+        tw, dw = si.make_weights(ts, wl["seeds"]["target"]), si.make_weights(ds, wl["seeds"]["draft"])
     if draft_is_target:
         ds, dw = ts, tw
     toks = si.make_prefix(ts, 5, n_prefix, wl["seeds"]["prefix"])
@@ -44,13 +49,14 @@ def test_ssd_cycles_in_lockstep_with_oracle(workload, tol, beta):
     run_cycles_in_lockstep(workload, tol, beta, K=3, steps=10, require_both=True)
 
 
-def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix=40, sharp_steps=True):
+def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix=40, sharp_steps=True, models=None):
     import paper_2505_15380_amd as ssd
     from oracle import decoder as OD, ssd as OS
     from oracle.accept import sample_canonical, accept_canonical
     from oracle.philox import uniform24
     from oracle.warp import warp_probs
-    sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos) = make_session(workload, K, beta=beta, steps=steps, n_prefix=n_prefix)
+    sess, (ts, tw, ds, dw, toks, cfg, dcfg, max_pos) = make_session(workload, K, beta=beta, steps=steps, n_prefix=n_prefix,
+                                                                    models=models)
     t, d = OD.Model(ts, tw), OD.Model(ds, dw)
     tc, dc = OD.Cache(ts, max_pos), OD.Cache(ds, max_pos)
     OD.prefill(t, tc, toks[:-1]); OD.prefill(d, dc, toks[:-1])
@@ -99,6 +105,25 @@ def run_cycles_in_lockstep(workload, tol, beta, K, steps, require_both, n_prefix
     sess.draft_paths_seen = draft_paths
     sess.accepted_seen = ns
     return sess
+
+
+def test_cycles_with_a_layer_inheritance_draft_in_lockstep_with_oracle():
+    """The draft the paper builds (Sec. 2.3): the target's lower and upper layers, its embeddings and its head, here
+    without the fine-tuning: a 6-layer target of the small bf16 shape with a peaked head, draft = layers 0, 1, 4, 5.
+    Cycles in lockstep with the oracle as above; such a draft agrees with its target far more often than an unrelated
+    one, so full acceptances and rejections both occur at beta = 0."""
+    ts = si.model_shape("mini_bf16")
+    ts["n_layers"] = 6
+    tw = si.make_weights(ts, 9100)
+    tw["head"] = si.round_to_bf16(tw["head"] * np.float32(6.0))           # peaked distributions
+    ds, dw = si.correlated_draft_weights(ts, tw, 4, n_lower=2)
+    sess = run_cycles_in_lockstep("mini", 2e-2, 0.0, K=3, steps=14, require_both=True, sharp_steps=False,
+                                  models=(ts, tw, ds, dw))
+    assert sess.kv.last_forward_path() == 3
+    # and the same pair under the tolerance of Eq. 5: more is accepted (Table 3's trend), still in lockstep
+    sess2 = run_cycles_in_lockstep("mini", 2e-2, 0.4, K=3, steps=14, require_both=False, sharp_steps=False,
+                                   models=(ts, tw, ds, dw))
+    assert sum(sess2.accepted_seen) >= sum(sess.accepted_seen)
 
 
 @pytest.mark.parametrize("workload", ["tiny", "mini"])
@@ -442,3 +467,30 @@ def test_captured_cycle_replays_like_the_eager_cycle(workload, K, cycles):
         assert a.kv.state(0)["table"] == b.kv.state(0)["table"]
         assert a.kv.free_stack() == b.kv.free_stack()
     torch.cuda.synchronize()
+
+
+def test_verify_of_512_rows_against_the_oracle():
+    """64 ragged sequences x (K+1 = 8) rows = 512 rows, the most one verification takes, on the small bf16 shape: every
+    sequence's logits, probabilities and decision against the oracle, block tables and free stack against the allocator
+    model, two steps (the second after 64 different commits)."""
+    from tests.parity import Pair, verify_parity_step
+    shape = si.model_shape("mini_bf16")
+    B, K, steps = 64, 7, 2
+    rng0 = np.random.default_rng(64)
+    lens = [int(n) for n in rng0.integers(18, 140, size=B)]
+    cap = max(lens) + steps * (K + 1) + 20
+    pair = Pair("mini_bf16", 778, cap, max_seqs=B, max_rows=K + 1, block_tokens=16)
+    for b in range(B):
+        pair.prefill(b, si.make_prefix(shape, 3, lens[b] - 3, 1200 + b))
+    rng = np.random.default_rng(9)
+    cfg = dict(beta=0.2, temperature=1.0, top_k=0, greedy=False, seed=13)
+    worst, ns = 0.0, []
+    for s in range(steps):
+        res = verify_parity_step(pair, cfg, K, s, rng, 2e-2, 2e-2, seqs=tuple(range(B)))
+        assert pair.kv.last_forward_path() == 1
+        worst = max(worst, max(r["dlogits"] for r in res))
+        ns += [r["n"] for r in res]
+        for b in (0, 17, 63):
+            pair.check_state(b, 2e-2, layers=[shape["n_layers"] - 1])
+        pair.check_free_stack()
+    assert 0 < worst < 2e-2 and len(set(ns)) > 2

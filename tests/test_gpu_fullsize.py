@@ -102,22 +102,80 @@ def _sampled_batch_parity(workload, sample, atol, max_prefix=None, atol_exact=No
 @pytest.mark.timeout(900)
 def test_half_b_batch16_sampled_parity():
     """The batch-16 configuration (ragged prefixes in [256, 4096], K=6, 16-token blocks) at full size: 112 rows in one
-    verification; the oracle checks the two shortest sequences."""
+    verification; the oracle checks the shortest and the longest sequence (3789 positions: fifteen 256-key attention
+    parts on the path with one launch per operator)."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    path = _sampled_batch_parity("half_b_batch16", sample=(0, 1), atol=2e-2)
+    path = _sampled_batch_parity("half_b_batch16", sample=(0, 15), atol=2e-2)
     assert path == 1                     # more than 16 rows: one launch per operator
 
 
 @pytest.mark.timeout(900)
 def test_half_b_long_prefix_topk_parity():
-    """The long-utterance configuration at full size: prefix 4096 (17 attention parts of 256 keys), K=8 (nine rows),
-    top-k 25 on the target; one verification against the oracle, through the barrier-free kernel."""
+    """The long-utterance configuration at full size: prefix 4096 (17 attention parts of 256 keys), top-k 25 on the
+    target; one verification each at K = 8, 2 and 12 (nine, three and thirteen rows; K = 4 is what every other
+    full-size test runs) against the oracle, through the barrier-free kernel."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from tests.parity import run_verify_parity
-    r = run_verify_parity("half_b_long", steps=1, K=8, beta=0.2, atol_logits=2e-2, atol_probs=2e-2, top_k=25, verbose=True)
+    r = run_verify_parity("half_b_long", steps=3, K=[8, 2, 12], beta=0.2, atol_logits=2e-2, atol_probs=2e-2, top_k=25,
+                          verbose=True)
     assert r["path"] == 3
+
+
+@pytest.mark.timeout(900)
+def test_half_b_long_prefix_topk_draft_step():
+    """A draft step (Eq. 2-3) of the long-utterance configuration at full size: the 4-layer draft at prefix 4096 with
+    top-k 25.  The kept set is an integer decision taken in the kernel's precision: it must have exactly 25 entries and
+    be a top-25 of the oracle's logits up to the tolerance; on that set the probabilities must match, and the drawn
+    token must be the canonical draw from the kernel's own row."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import numpy as np
+    import paper_2505_15380_amd as ssd
+    import synth_inputs as si
+    from oracle import decoder as OD, ssd as OS
+    from oracle.accept import sample_canonical
+    wl = si.workload("half_b_long")
+    ds = si.model_shape(wl["draft"])
+    dw = si.make_weights(ds, wl["seeds"]["draft"])
+    toks = si.make_prefix(ds, *wl["prefix"], wl["seeds"]["prefix"])
+    max_pos = len(toks) + 64
+    model = ssd.Model(ds, ssd.upload_weights(ds, dw), max_pos)
+    kv = ssd.KVCache(model, 1, 256, -(-max_pos // 16), 16, -(-max_pos // 16), 2)
+    ssd.ssd_prefill(model, kv, 0, torch.from_numpy(toks).cuda())
+    V = ds["vocab"]
+    tok = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pd = torch.zeros((1, V), dtype=torch.float32, device="cuda")
+    cfg = ssd.sample_config(temperature=1.0, top_k=25, seed=wl["seeds"]["rng"] + 1)
+    ssd.ssd_draft_step(model, kv, 1, cfg, 3, 1, tok, 1, pd, V)
+    torch.cuda.synchronize()
+    assert kv.last_forward_path() == 3                      # 4095 cached positions: attention in 256-key parts
+    gp = pd.cpu().numpy()[0]
+    om = OD.Model(ds, dw)
+    oc = OD.Cache(ds, max_pos)
+    OD.prefill(om, oc, toks[:-1])
+    lo = OD.forward_rows(om, oc, [int(toks[-1])])[0]
+    kept = np.flatnonzero(gp > 0)
+    assert len(kept) == 25
+    dropped = np.setdiff1d(np.arange(V), kept)
+    assert lo[kept].min() >= lo[dropped].max() - 2 * 2e-2, "the kept set is not a top-25 of the oracle's logits"
+    ref = np.exp(lo[kept] - lo[kept].max())
+    ref /= ref.sum()
+    assert np.abs(gp[kept] - ref).max() <= 2e-2
+    assert int(tok[0]) == sample_canonical(gp, OS.draft_uniform(wl["seeds"]["rng"] + 1, 0, 3, 1))
+    st = kv.state(0)
+    assert st["len"] == len(toks) and st["pending"] == [int(tok[0])]
+
+
+@pytest.mark.timeout(900)
+def test_half_b_batch64_sampled_parity():
+    """Beyond the benchmark plan: 64 sequences x 8 rows = 512 rows in one verification (ragged prefixes in
+    [256, 2048]); the oracle checks the shortest sequence."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    path = _sampled_batch_parity("half_b_batch64", sample=(0,), atol=2e-2)
+    assert path == 1
 
 
 @pytest.mark.timeout(1100)
