@@ -443,6 +443,11 @@ extern "C" int ssd_kv_create(const ssd_model* m, int max_seqs, int max_rows, int
   if (e == hipSuccess)
     e = hipMemsetAsync(kv->tickets, 0, sizeof(int32_t) * std::max(m->c.d_model / 32 + 1, max_seqs * max_rows * m->c.n_kv_heads),
                        (hipStream_t)stream);
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+      kv->cus = cus;                                       // (every path sizes its k-splits by it)
+  }
   // The persistent forward needs: bf16 storage, head_dim 64, 16-token blocks, <= 16 query heads per kv head.
   kv->persistent_wgs = 0;
   if (e == hipSuccess && m->c.dtype == SSD_DTYPE_BF16 && m->c.head_dim == 64 && block_tokens == 16 && m->layer_stride &&
