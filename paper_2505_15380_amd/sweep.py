@@ -1,5 +1,5 @@
-"""Tolerance / draft-length sweep of whole SSD cycles on one GPU (the trade-off of Sec. 3.3 and Table 2, in
-throughput terms only: no audio is produced here, so the quality columns of the paper have no counterpart).
+"""Tolerance / draft-length sweep of whole SSD cycles on one GPU (the trade-offs of Sec. 4.3 with Table 3 - the
+tolerance factor - and of Sec. 4.4 with Fig. 3 - the draft length - in throughput terms only: no audio is produced here, so the quality columns of the paper have no counterpart).
 
     python -m paper_2505_15380_amd.sweep [--cycles N] [--prefix P] [--head-scale S] [--top-k k] [--independent-draft]
 
