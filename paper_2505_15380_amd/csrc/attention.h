@@ -21,6 +21,7 @@ struct AttnArgs {
   float* ml_part;       // [M][nq][NC][2]
   int NC;               // chunk capacity of the partial buffers
   void* out;            // [M][nq*hd] (combine)
+  int split_kt;         // > 0: `out` is written as split rows (common.h) with this many k-tiles per row (nq*hd / 32)
   int nparts, tiles_per_wg;   // k_attn_part_mfma: grid.x = nparts x groups of tiles_per_wg row tiles (a multiple of 4)
 };
 
@@ -124,7 +125,10 @@ __global__ void __launch_bounds__(WAVE) k_attn_combine(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < (HD + WAVE - 1) / WAVE; ++i) {
     const int d = lane + i * WAVE;
-    if (d < HD) AT::st(out + d, o[i] / l);
+    if (d < HD) {
+      if (a.split_kt > 0) st_split_value((bf16_t*)a.out, a.split_kt, m, hq * HD + d, o[i] / l);
+      else AT::st(out + d, o[i] / l);
+    }
   }
 }
 
@@ -176,6 +180,8 @@ __device__ __forceinline__ void attn_load_chunk(const AttnArgs& a, const bf16_t*
 template <int HD>
 __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
   constexpr int KS = HD / 32, DT = HD / 16, NF = 4 * KS + 2 * DT;     // fragments of a chunk: 16 (HD 64) or 32 (HD 128)
+  // A wave's P tile, 16 rows x 64 keys: row r keeps key column c at c ^ 4 (r & 7), so that the 16-byte reads of eight
+  // consecutive rows fall into distinct banks (unswizzled they all hit the same four)
   __shared__ __attribute__((aligned(16))) float Pw[4][16 * 64];
   __shared__ u32x4 KV[4][NF][64];                        // the part's fragments, [chunk][fragment][lane]
   const int part = blockIdx.x % a.nparts, tgroup = blockIdx.x / a.nparts, kvh = blockIdx.y, brel = blockIdx.z;
@@ -228,14 +234,25 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
       pos[r] = qr < RG ? a.rows.pos[m_first + qr / G] : -1;
     }
   };
-  u32x4 qraw[KS][2];
-  int pos[4];
-  if (rt_begin + uw < rt_end) { load_q(rt_begin + uw, qraw); load_pos(rt_begin + uw, pos); }
+  // position of the last row of tile rt (rows ascend in position: what the tile reaches)
+  auto tile_reach = [&](int rt) { return a.rows.pos[m_first + (min(16 * rt + 16, RG) - 1) / G]; };
+  u32x4 qraw[KS][2], qnext[KS][2];
+  int pos[4], pnext[4], reach = -1, reach_next = -1;
+  if (rt_begin + uw < rt_end) { load_q(rt_begin + uw, qraw); load_pos(rt_begin + uw, pos); reach = tile_reach(rt_begin + uw); }
   __syncthreads();
   for (int rt = rt_begin + uw; rt < rt_end; rt += 4) {
-    if (rt != rt_begin + uw) { load_q(rt, qraw); load_pos(rt, pos); }
-    // causal skip: positions ascend with the row, so a tile whose last row does not reach the part has nothing here
-    if (a.rows.pos[m_first + (min(16 * rt + 16, RG) - 1) / G] < pbase) continue;
+    if (rt != rt_begin + uw) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { qraw[ks][0] = qnext[ks][0]; qraw[ks][1] = qnext[ks][1]; }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pos[r] = pnext[r];
+      reach = reach_next;
+    }
+    // the wave's next tile travels while this one is worked on
+    if (rt + 4 < rt_end) { load_q(rt + 4, qnext); load_pos(rt + 4, pnext); reach_next = tile_reach(rt + 4); }
+    __builtin_amdgcn_sched_barrier(0);
+    // causal skip: a tile whose last row does not reach the part has nothing here
+    if (reach < pbase) continue;
     SplitA qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = split_bf16(qraw[ks][0], qraw[ks][1]);
@@ -277,7 +294,7 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const float p = (s[t][r] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(s[t][r] - mnew);
-          P[(4 * g + r) * 64 + 16 * t + c16] = p;
+          P[(4 * g + r) * 64 + ((16 * t + c16) ^ (((4 * g + r) & 7) << 2))] = p;
           sum += p;
         }
         mrow[r] = mnew;
@@ -291,8 +308,8 @@ __global__ void __launch_bounds__(BLOCK) k_attn_part_mfma(AttnArgs a) {
         for (int r = 0; r < 4; ++r) oacc[dt][r] *= alpha[r];
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const u32x4* pp = (const u32x4*)(P + c16 * 64 + ks * 32 + g * 8);
-        const SplitA pf = split_bf16(pp[0], pp[1]);
+        const int pc = ks * 32 + g * 8, sw = (c16 & 7) << 2;
+        const SplitA pf = split_bf16(*(const u32x4*)(P + c16 * 64 + (pc ^ sw)), *(const u32x4*)(P + c16 * 64 + ((pc + 4) ^ sw)));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           const bf16x8 vv = __builtin_bit_cast(bf16x8, KV[c][4 * KS + ks * DT + dt][lane]);
@@ -336,6 +353,11 @@ __global__ void __launch_bounds__(WAVE) k_attn_combine_parts(AttnArgs a) {
     l = fmaf(a.ml_part[(base + p) * 2 + 1], w, l);
 #pragma unroll
     for (int i = 0; i < HD / 64; ++i) o[i] = fmaf(a.o_part[(base + p) * HD + lane + i * WAVE], w, o[i]);
+  }
+  if (a.split_kt > 0) {
+#pragma unroll
+    for (int i = 0; i < HD / 64; ++i) st_split_value((bf16_t*)a.out, a.split_kt, m, hq * HD + lane + i * WAVE, o[i] / l);
+    return;
   }
   typename AT::T* out = (typename AT::T*)a.out + (size_t)m * a.nq * HD + hq * HD;
 #pragma unroll

@@ -179,6 +179,21 @@ __device__ __forceinline__ SplitA split_bf16(const u32x4 a, const u32x4 b) {
   return s;
 }
 
+// "Split rows": GEMM operand rows [M][K] kept as the matrix core takes them, for the kernels that serve many rows
+// (gemm_rows.h).  Value x of (row, k) is stored as hi = upper 16 bits of x and lo = bf16(x - hi); the fragment of row
+// tile mt = row / 16 and k-tile kt = k / 32 is 64 lanes x 8 bf16 with lane = row % 16 + 16 * ((k % 32) / 8), element k % 8:
+// 1 KB of hi followed by 1 KB of lo, fragments ordered [mt][kt].  A wave loads a fragment with one contiguous 16-byte
+// load per lane.  Index (in bf16 elements) of the hi value; the lo value is 512 elements further.
+__device__ __forceinline__ size_t split_index(int row, int k, int KT) {
+  return ((size_t)((row >> 4) * KT + (k >> 5)) * 2) * 512 + (size_t)(((row & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
+}
+__device__ __forceinline__ void st_split_value(bf16_t* base, int KT, int row, int k, float x) {
+  const uint32_t u = __float_as_uint(x), h = u & 0xFFFF0000u;
+  const size_t i = split_index(row, k, KT);
+  base[i] = (bf16_t)(h >> 16);
+  base[i + 512] = f_to_bf16(x - __uint_as_float(h));
+}
+
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Make `seq` own the blocks that cover `tokens` positions (one thread).

@@ -40,6 +40,7 @@ struct GemmArgs {
   int layer, nq;
   // EPI_SWIGLU
   void* act;            // [M][N]
+  int act_split_kt;     // > 0: act is written as split rows (common.h) with this many k-tiles per row (N / 32)
 };
 
 // ------------------------------------------------------------------------------------------ epilogues
@@ -56,7 +57,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& g, int t0, int t1,
     const int n = t0 * 16 + col;
     if (n < g.N) {
       const float s = v0 / (1.0f + expf(-v0));
-      AT::st((typename AT::T*)g.act + (size_t)row * g.N + n, s * v1);
+      if (g.act_split_kt > 0) st_split_value((bf16_t*)g.act, g.act_split_kt, row, n, s * v1);
+      else AT::st((typename AT::T*)g.act + (size_t)row * g.N + n, s * v1);
     }
   } else {  // EPI_QKV: the two tiles hold dims d and d + hd/2 of one head
     const int hd = g.kv.hd, half = hd >> 1;
@@ -238,9 +240,8 @@ struct WideArgs {
   int n_slices, n_rowg, n_colg;
 };
 
-// W waves per workgroup, NPW column-tile pairs per wave.  (8, 1) is the shape described above; (4, 2) is for hundreds
-// of rows: a wave's activation fragment then feeds 8 MFMAs instead of 4 (half the LDS bandwidth per MFMA) and two
-// workgroups fit a CU, so one stages while the other contracts.
+// W waves per workgroup, NPW column-tile pairs per wave; (8, 1) is the shape described above and the one that is
+// launched (some tens of rows up to 255; from 256 rows on the kernels of gemm_rows.h take over).
 template <int MTW, int EPI, int W, int NPW>
 __global__ void __launch_bounds__(W * 64, W == 4 ? 2 : 1) k_gemm_wide(GemmArgs g, WideArgs wa) {
   extern __shared__ u32x4 afrag[];                        // two buffers of [(mt * KC + kt in chunk) * 2 + {hi, lo}][lane]

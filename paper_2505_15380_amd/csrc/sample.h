@@ -75,6 +75,49 @@ __global__ void __launch_bounds__(BLOCK) k_add_norm(float* h, const float* part,
   for (int i = threadIdx.x; i < d; i += BLOCK) AT::st(xr + i, hr[i] * inv * gain[i]);
 }
 
+// The same for the kernels that serve many rows: the normalised row goes out as split rows (see common.h), eight
+// consecutive columns per thread (d <= 4096).
+__global__ void __launch_bounds__(BLOCK) k_add_norm_split(float* h, const float* part, int n_part, size_t part_stride,
+                                                          const float* gain, float eps, bf16_t* xs, int d) {
+  __shared__ float s4[4];
+  const int m = blockIdx.x, KT = d >> 5, nslot = d >> 3;
+  float* hr = h + (size_t)m * d;
+  float v[2][8];
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int sl = threadIdx.x + q * BLOCK;
+    if (sl < nslot) {
+      const float4 x0 = *(const float4*)(hr + sl * 8), x1 = *(const float4*)(hr + sl * 8 + 4);
+      v[q][0] = x0.x; v[q][1] = x0.y; v[q][2] = x0.z; v[q][3] = x0.w; v[q][4] = x1.x; v[q][5] = x1.y; v[q][6] = x1.z; v[q][7] = x1.w;
+      const float* pp = part + (size_t)m * d + sl * 8;
+      for (int s0 = 0; s0 < n_part; ++s0) {                 // ascending split order, as k_add_norm
+        const float4 p0 = *(const float4*)(pp + (size_t)s0 * part_stride), p1 = *(const float4*)(pp + (size_t)s0 * part_stride + 4);
+        v[q][0] += p0.x; v[q][1] += p0.y; v[q][2] += p0.z; v[q][3] += p0.w; v[q][4] += p1.x; v[q][5] += p1.y; v[q][6] += p1.z; v[q][7] += p1.w;
+      }
+      *(float4*)(hr + sl * 8) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
+      *(float4*)(hr + sl * 8 + 4) = make_float4(v[q][4], v[q][5], v[q][6], v[q][7]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss = fmaf(v[q][i], v[q][i], ss);
+    }
+  }
+  const float tot = block_sum(ss, s4);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int sl = threadIdx.x + q * BLOCK;
+    if (sl < nslot) {
+      uint32_t y[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] = __float_as_uint(v[q][i] * inv * gain[sl * 8 + i]);
+      const SplitA sp = split_bf16(u32x4{y[0], y[1], y[2], y[3]}, u32x4{y[4], y[5], y[6], y[7]});
+      u32x4* o = (u32x4*)(xs + split_index(m, sl * 8, KT));
+      o[0] = __builtin_bit_cast(u32x4, sp.hi);
+      o[64] = __builtin_bit_cast(u32x4, sp.lo);            // 512 bf16 further
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------ warp + softmax
 __device__ __forceinline__ uint32_t order_key(float f) {      // larger float <-> larger key
   const uint32_t u = __float_as_uint(f);

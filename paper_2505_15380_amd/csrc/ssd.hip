@@ -17,6 +17,7 @@
 #include "attention.h"
 #include "common.h"
 #include "gemm.h"
+#include "gemm_rows.h"
 #include "persistent.h"
 #include "dataflow.h"
 #include "sample.h"
@@ -340,14 +341,15 @@ static size_t kv_layout(const ssd_model* m, int max_seqs, int max_rows, int n_bl
   int32_t* rpos = cv.take<int32_t>(Mmax);
   int32_t* ract = cv.take<int32_t>(Mmax);
   int32_t* scratch_i = cv.take<int32_t>(2 * max_seqs);
+  const int Mpad = cdiv(Mmax, 16) * 16;                    // operand buffers also serve as split rows: whole row tiles
   float* h = cv.take<float>((size_t)Mmax * c.d_model);
-  void* xn = cv.take<float>((size_t)Mmax * c.d_model);
+  void* xn = cv.take<float>((size_t)Mpad * c.d_model);
   float* q = cv.take<float>((size_t)Mmax * nqd);
   float* o_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * c.head_dim);
   float* ml_part = cv.take<float>((size_t)Mmax * c.n_q_heads * NC * 2);
-  void* attn = cv.take<float>((size_t)Mmax * nqd);
+  void* attn = cv.take<float>((size_t)Mpad * nqd);
   float* part = cv.take<float>((size_t)MAX_SPLITS * Mmax * c.d_model);
-  void* act = cv.take<float>((size_t)Mmax * c.d_ffn);
+  void* act = cv.take<float>((size_t)Mpad * c.d_ffn);
   float* logits = cv.take<float>((size_t)Mmax * c.vocab);
   float* probs = cv.take<float>((size_t)Mmax * c.vocab);
   const int NP = cdiv(m->max_positions, ATT_PART);
@@ -576,33 +578,29 @@ static int launch_gemm(const ssd_model* m, GemmArgs g, int items, hipStream_t st
 }
 
 // Launch shape of k_gemm_wide (see gemm.h) for M rows: fewest row groups of at most 4 tiles, the largest staged chunk
-// that fits the LDS budget, and for k-split outputs one slice per chunk up to the partial buffer's capacity.  From 256
-// rows on: 4 waves x 2 pairs per wave, 4 row tiles and half the LDS budget, so that two workgroups share a CU.
+// that fits the LDS budget, and for k-split outputs one slice per chunk up to the partial buffer's capacity.
 struct WidePlan {
-  int mtw, grid, waves, npw;
+  int mtw, grid, waves;
   size_t lds;
   WideArgs wa;
 };
-static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices, bool big) {
+static WidePlan plan_wide(int M, int N, int K, bool partial, int mtw_forced, int max_slices) {
   WidePlan p;
   const int MT = cdiv(M, 16), KT = K / 32;
-  p.waves = big ? 4 : WIDE_WAVES;
-  p.npw = big ? 2 : 1;
+  p.waves = WIDE_WAVES;
   int n_rowg = cdiv(MT, 4);
   p.mtw = cdiv(MT, n_rowg);
   if (mtw_forced >= 1 && mtw_forced <= WIDE_MAX_MTW) p.mtw = mtw_forced;
-  if (big) p.mtw = 4;
   if (p.mtw == 5) p.mtw = 6;                              // instantiated: 1, 2, 3, 4, 6, 8
   if (p.mtw == 7) p.mtw = 8;
   n_rowg = cdiv(MT, p.mtw);
-  const int lds_budget = big ? WIDE_LDS_BYTES / 2 : WIDE_LDS_BYTES;
+  const int lds_budget = WIDE_LDS_BYTES;
   const int kc_slice = (lds_budget / 2048 / p.mtw) & ~3;                 // k-tiles per slice of a k-split output
   const int kc_max = (WIDE_SG * p.waves / p.mtw) & ~3;                   // k-tiles per staged chunk (two buffers of it)
   const int n_pairs = partial ? cdiv(cdiv(N, 16), 2) : cdiv(N, 16);
-  p.wa.n_colg = cdiv(n_pairs, p.waves * p.npw);
+  p.wa.n_colg = cdiv(n_pairs, p.waves);
   p.wa.n_rowg = n_rowg;
   p.wa.n_slices = partial ? std::min(max_slices, std::max(1, cdiv(KT, kc_slice))) : 1;
-  if (big && partial) p.wa.n_slices = std::min(p.wa.n_slices, std::max(1, cdiv(256, p.wa.n_colg * n_rowg)));   // a workgroup per CU is enough
   p.wa.slice_kt = (cdiv(KT, p.wa.n_slices) + 3) & ~3;
   p.wa.n_slices = cdiv(KT, p.wa.slice_kt);
   p.wa.KC = std::min(kc_max, p.wa.slice_kt);
@@ -616,8 +614,7 @@ static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
   static const hipError_t lds_ok = [] {                   // more than 64 KB of dynamic LDS is opt-in, once per process
     const void* fns[] = {(const void*)k_gemm_wide<1, EPI, 8, 1>, (const void*)k_gemm_wide<2, EPI, 8, 1>,
                          (const void*)k_gemm_wide<3, EPI, 8, 1>, (const void*)k_gemm_wide<4, EPI, 8, 1>,
-                         (const void*)k_gemm_wide<6, EPI, 8, 1>, (const void*)k_gemm_wide<8, EPI, 8, 1>,
-                         (const void*)k_gemm_wide<4, EPI, 4, 2>};
+                         (const void*)k_gemm_wide<6, EPI, 8, 1>, (const void*)k_gemm_wide<8, EPI, 8, 1>};
     for (const void* f : fns) {
       const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WIDE_LDS_BYTES);
       if (e != hipSuccess) return e;
@@ -626,21 +623,64 @@ static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
   }();
   if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
   const dim3 grid(p.grid), block(p.waves * 64);
-  if (p.waves == 4) {
-    hipLaunchKernelGGL((k_gemm_wide<4, EPI, 4, 2>), grid, block, p.lds, st, g, p.wa);
-  } else {
-    switch (p.mtw) {
-      case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      case 4: hipLaunchKernelGGL((k_gemm_wide<4, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      case 6: hipLaunchKernelGGL((k_gemm_wide<6, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      case 8: hipLaunchKernelGGL((k_gemm_wide<8, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
-      default: return fail(SSD_EINVAL, "no wide GEMM for %d row tiles per workgroup", p.mtw);
-    }
+  switch (p.mtw) {
+    case 1: hipLaunchKernelGGL((k_gemm_wide<1, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    case 2: hipLaunchKernelGGL((k_gemm_wide<2, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    case 3: hipLaunchKernelGGL((k_gemm_wide<3, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    case 4: hipLaunchKernelGGL((k_gemm_wide<4, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    case 6: hipLaunchKernelGGL((k_gemm_wide<6, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    case 8: hipLaunchKernelGGL((k_gemm_wide<8, EPI, 8, 1>), grid, block, p.lds, st, g, p.wa); break;
+    default: return fail(SSD_EINVAL, "no wide GEMM for %d row tiles per workgroup", p.mtw);
   }
   LAUNCH_CHECK();
   return SSD_OK;
+}
+
+// Launch of k_gemm_rows (gemm_rows.h), from 256 rows on.  The tile a workgroup owns is chosen for the fewest bytes per
+// workgroup at a workgroup per CU or fewer: 8 waves take 128 rows (64 below 384 rows) x 12 weight tiles of gate and up
+// or 8 of a k-split output; the QKV projection, whose epilogue wants a whole head in one wave, 4 waves x 64 rows x one
+// head.  k-split outputs get as many slices as give about one workgroup per CU.  Returns the number of slices (> 0).
+template <int EPI>
+static int launch_rows(const GemmArgs& g, int cus, int hd, bool partial, int max_slices, hipStream_t st) {
+  const int KT = g.K / 32, MT = cdiv(g.M, 16);
+  const int n_wt = EPI == EPI_SWIGLU ? 2 * cdiv(g.N, 16) : cdiv(g.N, 16);     // weight tiles in all (gate and up both count)
+  RowsPlan p;
+  auto slices = [&](int n_wg) {                            // a multiple of 8 slices (one XCD each), about a workgroup per CU
+    int ns = 1;
+    if (partial && KT >= 16 && max_slices >= 8) ns = (n_wg * 12 <= cus && KT >= 64 && max_slices >= 16) ? 16 : 8;
+    p.slice_kt = cdiv(KT, ns);
+    p.n_slices = cdiv(KT, p.slice_kt);
+  };
+  if constexpr (EPI == EPI_QKV) {
+    p.n_rowb = cdiv(MT, 4);
+    p.n_colb = cdiv(n_wt, hd / 16);
+    slices(1);
+    const dim3 grid(8 * cdiv(p.n_colb, 8) * p.n_rowb), block(256);
+    // Four waves leave room for several workgroups on a CU, and the dispatcher then packs them while other CUs idle; what a
+    // CU takes in per microsecond is what bounds these kernels.  An LDS request of more than half a CU's keeps it to one.
+    constexpr size_t ALONE = 84 * 1024;
+    static const hipError_t lds_ok = [] {
+      hipError_t e = hipFuncSetAttribute((const void*)k_gemm_rows<EPI, 1, 4, 4, 1, 6, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ALONE);
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)k_gemm_rows<EPI, 1, 8, 4, 1, 6, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ALONE);
+      return e;
+    }();
+    if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
+    if (hd == 64) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 4, 4, 1, 6, 1>), grid, block, ALONE, st, g, p);
+    else if (hd == 128) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 8, 4, 1, 6, 1>), grid, block, ALONE, st, g, p);
+    else return fail(SSD_ENOSUP, "no many-row QKV kernel for head_dim %d", hd);
+  } else {
+    constexpr int TN = EPI == EPI_SWIGLU ? 6 : 4;
+    const bool tall = MT >= 24;                            // 128 rows per workgroup from 384 rows on
+    p.n_rowb = cdiv(MT, tall ? 8 : 4);
+    p.n_colb = cdiv(n_wt, 2 * TN);
+    slices(p.n_colb * p.n_rowb);
+    const dim3 grid(p.n_slices > 1 ? 8 * cdiv(p.n_slices, 8) * p.n_colb * p.n_rowb : 8 * cdiv(p.n_colb, 8) * p.n_rowb), block(512);
+    if (tall) hipLaunchKernelGGL((k_gemm_rows<EPI, 2, TN, 4, 2, 6, 1>), grid, block, 0, st, g, p);
+    else hipLaunchKernelGGL((k_gemm_rows<EPI, 1, TN, 4, 2, 6, 1>), grid, block, 0, st, g, p);
+  }
+  LAUNCH_CHECK();
+  return p.n_slices;
 }
 
 static int pick_splits(int K, int npairs) {
@@ -657,7 +697,8 @@ static int launch_attn(AttnArgs a, int nchunks, int nkv, int B, int M, bool mfma
       const int nparts = cdiv(nchunks * ATT_CHUNK, ATT_PART_KEYS);
       // many query rows per sequence (prefill chunks): groups of row tiles get workgroups of their own
       const int ntiles = cdiv(a.rows.R * (a.nq / nkv), 16);
-      const int groups = std::max(1, std::min(cdiv(ntiles, 4), cdiv(2048, nparts * nkv * B)));
+      // (about two workgroups per CU: a group that stages a part's keys for more row tiles re-reads them less)
+      const int groups = std::max(1, std::min(cdiv(ntiles, 4), cdiv(512, nparts * nkv * B)));
       a.nparts = nparts;
       a.tiles_per_wg = (cdiv(ntiles, groups) + 3) & ~3;
       hipLaunchKernelGGL((k_attn_part_mfma<HD>), dim3(nparts * cdiv(ntiles, a.tiles_per_wg), nkv, B), dim3(BLOCK), 0, st, a);
@@ -828,27 +869,40 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
   // down projection: slices of the long k range per workgroup, if that still gives half the CUs a workgroup
   // (measured: 18.7 vs 44.6 us per launch on the 1.5B shape at 72 rows, 168 workgroups; 18.7 vs 17.5 us on the 0.5B
   // shape at 112 rows, where it has 80)
-  const bool big = M >= 256;
-  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, 0, MAX_SPLITS, big);
+  const WidePlan down_plan = plan_wide(M, d, c.d_ffn, true, 0, MAX_SPLITS);
   const bool wide_down = wide &&
                          2 * down_plan.wa.n_colg * down_plan.wa.n_rowg * down_plan.wa.n_slices >= kv->cus;
   const int gs_d = wide_down ? down_plan.wa.n_slices : splits_for(c.d_ffn);
+  // from 256 rows on (prefill chunks): the kernels whose waves each own row tiles x weight tiles (gemm_rows.h); every GEMM
+  // operand (normalised rows, attention output, SwiGLU output) is then kept as split rows
+  const bool rowsk = wide && M >= 256 && d <= 4096 && (hd == 64 || hd == 128);
+  auto add_norm = [&](int n_part_, const float* gain) -> int {
+    if (rowsk) hipLaunchKernelGGL(k_add_norm_split, dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part_, part_stride, gain,
+                                  c.rms_eps, (bf16_t*)kv->xn, d);
+    else hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part_, part_stride, gain,
+                            c.rms_eps, kv->xn, d);
+    LAUNCH_CHECK();
+    return SSD_OK;
+  };
   int n_part = 0;
   int rc;
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerW& L = m->layers[l];
-    hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride, L.ln1,
-                       c.rms_eps, kv->xn, d);
-    LAUNCH_CHECK();
+    if ((rc = add_norm(n_part, L.ln1))) return rc;
     GemmArgs g = g0;                                       // QKV + bias + rotary + cache write
     g.A = kv->xn; g.lda = d; g.W0 = L.wqkv; g.W1 = L.wqkv; g.N = nqkv; g.K = d; g.gs = 1;
     g.bias = L.bqkv; g.q = kv->q; g.layer = l;
-    { ProfScope ps(PROF_QKV, st); rc = launch_gemm<DT, EPI_QKV>(m, g, (nq + 2 * nkv) * (hd / 32), st); }
+    {
+      ProfScope ps(PROF_QKV, st);
+      if (rowsk) rc = std::min(0, launch_rows<EPI_QKV>(g, kv->cus, hd, false, 1, st));
+      else rc = launch_gemm<DT, EPI_QKV>(m, g, (nq + 2 * nkv) * (hd / 32), st);
+    }
     if (rc) return rc;
 
     AttnArgs a;
     a.q = kv->q; a.kv = kv->v; a.rows = rows; a.layer = l; a.nq = nq; a.scale = 1.0f / sqrtf((float)hd);
     a.o_part = kv->o_part; a.ml_part = kv->ml_part; a.NC = kv->NC; a.out = kv->attn;
+    a.split_kt = rowsk ? nqd / 32 : 0;
     {
       ProfScope ps(PROF_ATTN, st);
       if (hd == 32) rc = launch_attn<DT, 32>(a, nchunks, nkv, B, M, kv->attn_mfma, st);
@@ -860,20 +914,26 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
     g = g0;                                                // output projection -> k-split partials
     g.A = kv->attn; g.lda = nqd; g.W0 = L.wo; g.W1 = L.wo; g.N = d; g.K = nqd; g.gs = gs_o;
     g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
-    { ProfScope ps(PROF_O, st); rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_o, st); }
+    int np_o = gs_o;
+    {
+      ProfScope ps(PROF_O, st);
+      if (rowsk) { np_o = launch_rows<EPI_PARTIAL>(g, kv->cus, hd, true, MAX_SPLITS, st); rc = std::min(0, np_o); }
+      else rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_o, st);
+    }
     if (rc) return rc;
 
-    hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, gs_o, part_stride, L.ln2,
-                       c.rms_eps, kv->xn, d);
-    LAUNCH_CHECK();
+    if ((rc = add_norm(np_o, L.ln2))) return rc;
 
     g = g0;                                                // gate / up + SwiGLU
     g.A = kv->xn; g.lda = d; g.W0 = L.wgate; g.W1 = L.wup; g.N = c.d_ffn; g.K = d; g.gs = 1; g.act = kv->act;
+    g.act_split_kt = rowsk ? c.d_ffn / 32 : 0;
     {
       ProfScope ps(PROF_GATEUP, st);
-      if (wide) {                                          // many rows: activations shared through LDS (see gemm.h)
+      if (rowsk) {
+        rc = std::min(0, launch_rows<EPI_SWIGLU>(g, kv->cus, hd, false, 1, st));
+      } else if (wide) {                                          // many rows: activations shared through LDS (see gemm.h)
         // two row tiles per workgroup: measured best on both shapes (more workgroups beat fewer weight re-reads)
-        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, 2, 1, big), st);
+        rc = launch_wide<EPI_SWIGLU>(g, plan_wide(M, c.d_ffn, d, false, 2, 1), st);
       } else {
         rc = launch_gemm<DT, EPI_SWIGLU>(m, g, cdiv(c.d_ffn, 16), st);
       }
@@ -883,22 +943,22 @@ static int forward(const ssd_model* m, ssd_kv* kv, int seq0, int B, int R, int p
     g = g0;                                                // down projection -> k-split partials
     g.A = kv->act; g.lda = c.d_ffn; g.W0 = L.wdown; g.W1 = L.wdown; g.N = d; g.K = c.d_ffn; g.gs = gs_d;
     g.out = kv->part; g.out_split_stride = part_stride; g.ldo = d;
+    n_part = gs_d;
     {
       ProfScope ps(PROF_DOWN, st);
-      if (wide_down) rc = launch_wide<EPI_PARTIAL>(g, down_plan, st);
+      if (rowsk) { n_part = launch_rows<EPI_PARTIAL>(g, kv->cus, hd, true, MAX_SPLITS, st); rc = std::min(0, n_part); }
+      else if (wide_down) rc = launch_wide<EPI_PARTIAL>(g, down_plan, st);
       else rc = launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(d, 16), 2) * gs_d, st);
     }
     if (rc) return rc;
-    n_part = gs_d;
   }
   if (!with_head) return SSD_OK;
-  hipLaunchKernelGGL((k_add_norm<F32>), dim3(M), dim3(BLOCK), 0, st, kv->h, kv->part, n_part, part_stride,
-                     m->final_norm, c.rms_eps, kv->xn, d);
-  LAUNCH_CHECK();
+  if ((rc = add_norm(n_part, m->final_norm))) return rc;
   GemmArgs g = g0;
   g.A = kv->xn; g.lda = d; g.W0 = m->head; g.W1 = m->head; g.N = c.vocab; g.K = d; g.gs = 1;
   g.out = kv->logits; g.out_split_stride = 0; g.ldo = c.vocab;
   ProfScope ps(PROF_HEAD, st);
+  if (rowsk) return std::min(0, launch_rows<EPI_PARTIAL>(g, kv->cus, hd, false, 1, st));
   return launch_gemm<DT, EPI_PARTIAL>(m, g, cdiv(cdiv(c.vocab, 16), 2), st);
 }
 
