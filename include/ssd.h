@@ -95,7 +95,7 @@ int    ssd_model_destroy(ssd_model* m);
  * Pool layout (dtype elements): keys [layer][0][block][kv_head][token_in_block][head_dim], stored after the
  * rotary embedding; values [layer][1][block][kv_head][head_dim][token_in_block] (token-minor, the order the
  * matrix-core attention reads them in).  The pool must hold finite values (e.g. zeros) when handed over.  `max_rows` bounds the rows of one forward per sequence (K+1 for verify, the
- * chunk of a prefill); max_seqs*max_rows <= 512.  `pending_cap` is 1 for a target cache and 2 for a draft
+ * chunk of a prefill); max_seqs*max_rows <= 1024.  `pending_cap` is 1 for a target cache and 2 for a draft
  * cache (a draft may owe two tokens after a fully accepted cycle).  Blocks are handed out lowest id first;
  * see ssd_kv_state for the exact bookkeeping.  dev_ws must hold ssd_kv_workspace_bytes(). */
 size_t ssd_kv_pool_bytes(const ssd_model* m, int n_blocks, int block_tokens);

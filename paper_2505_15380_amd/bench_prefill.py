@@ -1,6 +1,6 @@
 """Latency of a prompt prefill (the decoder forward over the prefix that fills the cache before the first SSD cycle).
 
-    python -m paper_2505_15380_amd.bench_prefill [--workload half_b_k4] [--tokens 4096] [--rows 512] [--iters 3]
+    python -m paper_2505_15380_amd.bench_prefill [--workload half_b_k4] [--tokens 4096] [--rows 1024] [--iters 3]
 
 Prefills `--tokens` positions of the workload's target shape in launches of up to `--rows` rows (every operator its
 own launch: more rows than the persistent kernels take) and prints one JSON line: the whole prefill's time, tokens/s,
@@ -19,7 +19,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="half_b_k4")
     ap.add_argument("--tokens", type=int, default=4096)
-    ap.add_argument("--rows", type=int, default=512)
+    ap.add_argument("--rows", type=int, default=1024)
     ap.add_argument("--iters", type=int, default=3)
     args = ap.parse_args()
     import torch

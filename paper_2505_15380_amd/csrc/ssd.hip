@@ -284,7 +284,7 @@ extern "C" int ssd_model_destroy(ssd_model* m) {
 
 // ------------------------------------------------------------------------------------------------ kv
 constexpr int MAX_SPLITS = 16;   // capacity of the k-split partial buffer
-constexpr int MAX_ROWS = 512;
+constexpr int MAX_ROWS = 1024;
 
 struct ssd_kv {
   const ssd_model* m;
@@ -637,9 +637,10 @@ static int launch_wide(const GemmArgs& g, const WidePlan& p, hipStream_t st) {
 }
 
 // Launch of k_gemm_rows (gemm_rows.h), from 256 rows on.  The tile a workgroup owns is chosen for the fewest bytes per
-// workgroup at a workgroup per CU or fewer: 8 waves take 128 rows (64 below 384 rows) x 12 weight tiles of gate and up
-// or 8 of a k-split output; the QKV projection, whose epilogue wants a whole head in one wave, 4 waves x 64 rows x one
-// head.  k-split outputs get as many slices as give about one workgroup per CU.  Returns the number of slices (> 0).
+// workgroup at a workgroup per CU or fewer: 8 waves take 64, 128 or 256 rows (by the launch's rows) x 12 weight tiles
+// of gate and up or 8 of a k-split output; the QKV projection, whose epilogue wants a whole head in one wave, 4 waves
+// x 64 or 128 rows x one head.  k-split outputs get 8 slices, one per XCD (16 where that still leaves few workgroups).
+// Returns the number of slices (> 0).
 template <int EPI>
 static int launch_rows(const GemmArgs& g, int cus, int hd, bool partial, int max_slices, hipStream_t st) {
   const int KT = g.K / 32, MT = cdiv(g.M, 16);
@@ -652,31 +653,27 @@ static int launch_rows(const GemmArgs& g, int cus, int hd, bool partial, int max
     p.n_slices = cdiv(KT, p.slice_kt);
   };
   if constexpr (EPI == EPI_QKV) {
-    p.n_rowb = cdiv(MT, 4);
+    const int tm = MT >= 48 ? 2 : 1;                       // 64 rows x one head per workgroup, 128 rows from 768 rows on
+    p.n_rowb = cdiv(MT, 4 * tm);
     p.n_colb = cdiv(n_wt, hd / 16);
     slices(1);
     const dim3 grid(8 * cdiv(p.n_colb, 8) * p.n_rowb), block(256);
-    // Four waves leave room for several workgroups on a CU, and the dispatcher then packs them while other CUs idle; what a
-    // CU takes in per microsecond is what bounds these kernels.  An LDS request of more than half a CU's keeps it to one.
-    constexpr size_t ALONE = 84 * 1024;
-    static const hipError_t lds_ok = [] {
-      hipError_t e = hipFuncSetAttribute((const void*)k_gemm_rows<EPI, 1, 4, 4, 1, 6, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ALONE);
-      if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)k_gemm_rows<EPI, 1, 8, 4, 1, 6, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ALONE);
-      return e;
-    }();
-    if (lds_ok != hipSuccess) return fail(SSD_EHIP, "hipFuncSetAttribute: %s", hipGetErrorString(lds_ok));
-    if (hd == 64) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 4, 4, 1, 6, 1>), grid, block, ALONE, st, g, p);
-    else if (hd == 128) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 8, 4, 1, 6, 1>), grid, block, ALONE, st, g, p);
+    if (hd == 64 && tm == 1) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 4, 4, 1, 6, 1>), grid, block, 0, st, g, p);
+    else if (hd == 64) hipLaunchKernelGGL((k_gemm_rows<EPI, 2, 4, 4, 1, 6, 1>), grid, block, 0, st, g, p);
+    else if (hd == 128 && tm == 1) hipLaunchKernelGGL((k_gemm_rows<EPI, 1, 8, 4, 1, 6, 1>), grid, block, 0, st, g, p);
+    else if (hd == 128) hipLaunchKernelGGL((k_gemm_rows<EPI, 2, 8, 4, 1, 4, 1>), grid, block, 0, st, g, p);
     else return fail(SSD_ENOSUP, "no many-row QKV kernel for head_dim %d", hd);
   } else {
     constexpr int TN = EPI == EPI_SWIGLU ? 6 : 4;
-    const bool tall = MT >= 24;                            // 128 rows per workgroup from 384 rows on
-    p.n_rowb = cdiv(MT, tall ? 8 : 4);
+    // rows per workgroup: 64 below 384 rows, 128 up to 767, 256 from there on (the tile grows with the rows as long as
+    // about 200 workgroups remain: a workgroup's bytes per output fall, the number of busy CUs does not)
+    const int tm = MT >= 48 ? 4 : MT >= 24 ? 2 : 1;
+    p.n_rowb = cdiv(MT, 4 * tm);
     p.n_colb = cdiv(n_wt, 2 * TN);
     slices(p.n_colb * p.n_rowb);
     const dim3 grid(p.n_slices > 1 ? 8 * cdiv(p.n_slices, 8) * p.n_colb * p.n_rowb : 8 * cdiv(p.n_colb, 8) * p.n_rowb), block(512);
-    if (tall) hipLaunchKernelGGL((k_gemm_rows<EPI, 2, TN, 4, 2, 6, 1>), grid, block, 0, st, g, p);
+    if (tm == 4) hipLaunchKernelGGL((k_gemm_rows<EPI, 4, TN, 4, 2, 2, 1>), grid, block, 0, st, g, p);
+    else if (tm == 2) hipLaunchKernelGGL((k_gemm_rows<EPI, 2, TN, 4, 2, 6, 1>), grid, block, 0, st, g, p);
     else hipLaunchKernelGGL((k_gemm_rows<EPI, 1, TN, 4, 2, 6, 1>), grid, block, 0, st, g, p);
   }
   LAUNCH_CHECK();

@@ -8,8 +8,8 @@ from . import binding as B
 class SSDSession:
     def __init__(self, target_shape, target_w, draft_shape, draft_w, n_seqs, K, max_positions, cfg, dcfg,
                  block_tokens=16, n_blocks=None, max_rows=None, device="cuda"):
-        if max_rows is None:                     # rows per sequence and launch: prefill chunks (the library takes 512 rows in all)
-            max_rows = max(K + 1, 512 // n_seqs)
+        if max_rows is None:                     # rows per sequence and launch: prefill chunks (the library takes 1024 rows in all)
+            max_rows = max(K + 1, 1024 // n_seqs)
         self.K, self.n_seqs = K, n_seqs
         self.cfg, self.dcfg = cfg, dcfg
         self.target = B.Model(target_shape, B.upload_weights(target_shape, target_w, device), max_positions, device)

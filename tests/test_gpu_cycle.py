@@ -346,16 +346,18 @@ def test_batched_verify_many_rows_kernels(shape_name, gemm, attn, monkeypatch):
     assert 0 < worst < 2e-2
 
 
-@pytest.mark.parametrize("shape_name", ["mini_bf16", "mini128_bf16"])
-def test_prefill_in_large_chunks_then_verify(shape_name):
-    """Prefill of 700 tokens in chunks of 256 rows (many row tiles per sequence: groups of tiles per attention
-    workgroup, causal skipping of tiles that do not reach a part), cache contents against the oracle's, then two
-    verifications on top of it."""
+@pytest.mark.parametrize("shape_name,max_rows,n_tokens", [("mini_bf16", 256, 700), ("mini128_bf16", 256, 700),
+                                                          ("mini_bf16", 1024, 1100), ("mini128_bf16", 1024, 1100)])
+def test_prefill_in_large_chunks_then_verify(shape_name, max_rows, n_tokens):
+    """Prefill in chunks of 256 rows (700 tokens) and of 1024 rows (1100 tokens: one launch of 1024 rows, the most the
+    library takes, and a ragged one of 75) - many row tiles per sequence: groups of tiles per attention workgroup, causal
+    skipping of tiles that do not reach a part, the GEMM kernels for 256 rows and more at each of their tile heights -
+    cache contents against the oracle's, then two verifications on top of it."""
     from tests.parity import Pair, verify_parity_step
     shape = si.model_shape(shape_name)
     K = 4
-    pair = Pair(shape_name, 778, 800, max_seqs=1, max_rows=256, block_tokens=16)
-    pair.prefill(0, si.make_prefix(shape, 50, 650, 720))
+    pair = Pair(shape_name, 778, n_tokens + 100, max_seqs=1, max_rows=max_rows, block_tokens=16)
+    pair.prefill(0, si.make_prefix(shape, 50, n_tokens - 50, 720))
     assert pair.kv.last_forward_path() == 1
     pair.check_state(0, 2e-2)
     pair.check_free_stack()
@@ -421,8 +423,8 @@ def test_errors_are_reported_not_faulted():
     with pytest.raises(ssd.SSDError):
         ssd.ssd_verify(pair.gmodel, pair.kv, 2, torch.zeros((2, 7), dtype=torch.int32, device="cuda"),
                        torch.full((2, 7, V), 1.0 / V, dtype=torch.float32, device="cuda"), 7, cfg, 0)          # n_seqs > max_seqs
-    with pytest.raises(ssd.SSDError):                           # more than 512 rows per forward
-        ssd.KVCache(pair.gmodel, 33, 16, 40, 16, 4, 1)
+    with pytest.raises(ssd.SSDError):                           # more than 1024 rows per forward
+        ssd.KVCache(pair.gmodel, 65, 16, 80, 16, 4, 1)
 
 
 @pytest.mark.parametrize("workload,K,cycles", [("mini", 3, 80), ("tiny", 2, 0)])
