@@ -38,7 +38,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--beta", type=float, default=0.4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-batched", action="store_true", help="skip the batch-16 and batch-8 verification sub-records")
+    ap.add_argument("--no-batched", action="store_true", help="skip the batch-16 and batch-8 verification and the prefill sub-records")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="after the benchmark, run a plain elementwise copy kernel over this many MiB (3 launches): the "
                          "known-size reference that scales the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -221,6 +221,13 @@ def main():
                         "flops": r["gemm_flops"] + r["attention_flops"], "frac_mfma_bf16_peak": r["frac_of_bf16_mfma_peak"],
                         "per_operator_us": {k: v["us_per_verify"] for k, v in r["per_operator"].items()}}
             torch.cuda.empty_cache()
+        # ---- and the prompt prefill that precedes the cycles: 4096 tokens, 1024 rows per launch ------------------
+        from paper_2505_15380_amd import bench_prefill
+        r = bench_prefill.measure(argparse.Namespace(workload="half_b_k4", tokens=4096, rows=1024, iters=3), weights=tw)
+        rec["prefill"] = {k: r[k] for k in ("tokens", "rows_per_launch", "prefill_ms", "tokens_per_s", "forward_path",
+                                            "gemm_TFLOPs_between_events", "gemm_frac_of_bf16_mfma_peak")}
+        rec["prefill"]["per_operator_us_per_launch"] = {k: v["us_per_launch"] for k, v in r["per_operator"].items()}
+        torch.cuda.empty_cache()
 
     # ---- CPU oracle on a bounded sample of the same workload -------------------------------------------
     if not args.no_cpu_baseline:

@@ -21,14 +21,19 @@ def main():
     ap.add_argument("--tokens", type=int, default=4096)
     ap.add_argument("--rows", type=int, default=1024)
     ap.add_argument("--iters", type=int, default=3)
-    args = ap.parse_args()
+    print(json.dumps(measure(ap.parse_args())))
+
+
+def measure(args, weights=None):
+    """The record of one prefill (args: workload, tokens, rows, iters).  `weights`: the target's tensors when the caller has
+    them already."""
     import torch
     import paper_2505_15380_amd as ssd
     import synth_inputs as si
 
     wl = si.workload(args.workload)
     shape = si.model_shape(wl["target"])
-    w = si.make_weights(shape, wl["seeds"]["target"])
+    w = weights if weights is not None else si.make_weights(shape, wl["seeds"]["target"])
     n = args.tokens + 1                                   # the last token stays pending: n - 1 positions are written
     toks = torch.from_numpy(si.make_prefix(shape, n // 4, n - n // 4, wl["seeds"]["prefix"])).cuda()
     bt = 16
@@ -53,12 +58,12 @@ def main():
     d, hd, nq, nkv, ffn, L = (shape[k] for k in ("d_model", "head_dim", "n_q_heads", "n_kv_heads", "d_ffn", "n_layers"))
     gemm_flops = 2 * (n - 1) * L * (d * (nq + 2 * nkv) * hd + nq * hd * d + 3 * d * ffn)
     gemm_s = sum(per_kind[k]["us_per_launch"] * per_kind[k]["launches"] for k in ("qkv", "o", "gate_up", "down")) * 1e-6
-    print(json.dumps({
+    return {
         "workload": args.workload, "tokens": n - 1, "rows_per_launch": args.rows, "forward_path": kv.last_forward_path(),
         "prefill_ms": round(ms, 2), "tokens_per_s": round((n - 1) / (ms * 1e-3), 1), "per_operator": per_kind,
         "gemm_flops": gemm_flops, "gemm_TFLOPs_between_events": round(gemm_flops / gemm_s / 1e12, 1),
         "gemm_frac_of_bf16_mfma_peak": round(gemm_flops / gemm_s / 2.5e15, 4),
-    }))
+    }
 
 
 if __name__ == "__main__":
