@@ -347,9 +347,11 @@ def test_batched_verify_many_rows_kernels(shape_name, gemm, attn, monkeypatch):
 
 
 @pytest.mark.parametrize("shape_name,max_rows,n_tokens", [("mini_bf16", 256, 700), ("mini128_bf16", 256, 700),
+                                                          ("mini_bf16", 400, 777), ("mini128_bf16", 300, 777),
                                                           ("mini_bf16", 1024, 1100), ("mini128_bf16", 1024, 1100)])
 def test_prefill_in_large_chunks_then_verify(shape_name, max_rows, n_tokens):
-    """Prefill in chunks of 256 rows (700 tokens) and of 1024 rows (1100 tokens: one launch of 1024 rows, the most the
+    """Prefill in chunks of 256 rows (700 tokens), of 400 and 300 rows (777 tokens: launches whose last row tile is
+    ragged, 400 + 376 and 300 + 300 + 176 rows) and of 1024 rows (1100 tokens: one launch of 1024 rows, the most the
     library takes, and a ragged one of 75) - many row tiles per sequence: groups of tiles per attention workgroup, causal
     skipping of tiles that do not reach a part, the GEMM kernels for 256 rows and more at each of their tile heights -
     cache contents against the oracle's, then two verifications on top of it."""
