@@ -27,14 +27,17 @@ def test_half_b_verify_parity_full_size_matched_cache_format():
     assert 0 < r["dlogits"] < 4e-3
 
 
-def _sampled_batch_parity(workload, sample, atol, max_prefix=None, atol_exact=None):
+def _sampled_batch_parity(workload, sample, atol, max_prefix=None, atol_exact=None, prefill_rows=0, atol_kv=3e-2):
     """All sequences of a batched workload on the GPU in the launch configuration of that batch (every sequence
     prefilled, one verification of all of them together); the oracle follows only the sequences in `sample`
     (sequences are independent, so each can be checked on its own): logits and probabilities of its K+1 rows
     within tolerance, decision bit-exact given the GPU's probabilities, committed length per sequence.
     With atol_exact the comparison is made twice: against the oracle whose cache stores keys/values as the bf16
     pool does (tolerance atol: what the arithmetic costs) and against the exact oracle (tolerance atol_exact: that
-    plus what the cache format of the configuration costs, which no implementation can avoid)."""
+    plus what the cache format of the configuration costs, which no implementation can avoid).
+    prefill_rows > 0: the first sampled sequence's prompt is also prefilled on its own in launches of that many rows (the
+    kernels for 256 rows and more at the configuration's full shape) and the first and last layer's keys / values are
+    compared with the oracle's cache, which this test has anyway."""
     import numpy as np
     import paper_2505_15380_amd as ssd
     import synth_inputs as si
@@ -84,6 +87,19 @@ def _sampled_batch_parity(workload, sample, atol, max_prefix=None, atol_exact=No
             de = float(np.abs(g_logits[b] - e["logits"]).max())
             assert de <= atol_exact, f"seq {b}: logits differ from the exact oracle by {de}"
             print(f"seq {b}: max|dlogits| vs exact oracle {de:.3g}")
+        if prefill_rows and b == picked[0]:
+            n = len(toks[b]) - 1
+            kv1 = ssd.KVCache(gmodel, 1, prefill_rows, -(-(n + 8) // bt) + 2, bt, -(-max_pos // bt), 1)
+            ssd.ssd_prefill(gmodel, kv1, 0, torch.from_numpy(toks[b]).cuda())
+            torch.cuda.synchronize()
+            assert kv1.last_forward_path() == 1 and kv1.state(0)["len"] == n
+            dkv = 0.0
+            for l in (0, shape["n_layers"] - 1):
+                gk, gv = kv1.gather(0, l, n)
+                dkv = max(dkv, float(np.abs(gk - oc.k[l, :n]).max()), float(np.abs(gv - oc.v[l, :n]).max()))
+            print(f"seq {b}: prefill of {n} positions in launches of {prefill_rows} rows: keys/values within {dkv:.3g} of the oracle's")
+            assert dkv <= atol_kv, f"seq {b}: prefilled keys/values differ from the oracle's by {dkv}"
+            del kv1
         dl = float(np.abs(g_logits[b] - o["logits"]).max())
         dp = float(np.abs(g_probs[b] - o["pt"]).max())
         worst = max(worst, dl)
@@ -106,7 +122,7 @@ def test_half_b_batch16_sampled_parity():
     parts on the path with one launch per operator)."""
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    path = _sampled_batch_parity("half_b_batch16", sample=(0, 15), atol=2e-2)
+    path = _sampled_batch_parity("half_b_batch16", sample=(0, 15), atol=2e-2, prefill_rows=512)
     assert path == 1                     # more than 16 rows: one launch per operator
 
 
@@ -186,7 +202,7 @@ def test_one_half_b_batch8_sampled_parity():
         pytest.skip("no GPU")
     # bf16 storage of keys/values alone moves this shape's logits by 0.021 (oracle against oracle), so the exact
     # oracle is met within 4e-2 only; against the oracle with the same cache format the arithmetic must hold 2e-2
-    path = _sampled_batch_parity("one_half_b_batch8", sample=(0,), atol=2e-2, atol_exact=4e-2)
+    path = _sampled_batch_parity("one_half_b_batch8", sample=(0,), atol=2e-2, atol_exact=4e-2, prefill_rows=1024)
     assert path == 1
 
 
