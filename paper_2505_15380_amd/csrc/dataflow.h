@@ -590,26 +590,27 @@ __device__ __forceinline__ bool df_mlp_phase(const DArgs& a, const uint32_t tag,
 }
 
 // Sum of the ffn/32 down-projection partials in ascending order, residual, and the operand / statistics of the next
-// RMSNorm.  Task = (row, 32 output columns); thread (column c, group g of 8) sums the partials of its group, the
-// groups meet in LDS in ascending order.
-constexpr int DF_RW = 20;                 // partials a thread keeps in flight
+// RMSNorm.  Task = (row, 32 output columns) on a whole workgroup; thread (column c, group g of 16) sums the partials of
+// its group, the groups meet in LDS in ascending order.  (With a task per 4-wave unit and 8 groups a thread had 19
+// words in flight and two tasks polled through one CU: 30 us more per five-row forward.)
+constexpr int DF_RG = 16;                 // groups of partials per task: 512 threads = 32 columns x 16 groups
+constexpr int DF_RW = 10;                 // partials a thread keeps in flight
 __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, const uint32_t tag, int layer, const u64* part2, uint32_t tag2, const u64* h_in,
                                                 u64* h_out, u64* hg_out, u64* sq_out, const float* gain_next, int shift,
                                                 uint32_t* lds, int* sdead, int slot) {
   int tid = threadIdx.x;
   asm volatile("" : "+v"(tid));
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), usel = wave >> 2, ut = tid & 255;
-  const int unit = blockIdx.x * 2 + usel, NU = gridDim.x * 2;
+  const int NW = gridDim.x;
   const int M = a.rows.M, d = a.d, np = d >> 5, nW = a.ffn >> 5, PR = (int)(a.st_h / a.d);
-  const int tasks = M * np, rounds = (tasks + NU - 1) / NU;
-  const int uitem = df_item_of_unit(unit, shift, NU);
-  float* rs = (float*)(lds + DF_AW + DF_SQ_WORDS) + usel * 2048;      // [8 groups][32]
-  const int c = ut & 31, grp = ut >> 5;
-  const int per = (nW + 7) >> 3;
+  const int tasks = M * np, rounds = (tasks + NW - 1) / NW;
+  const int witem = df_item_of_unit(blockIdx.x, shift >> 1, NW);     // a task has the whole workgroup
+  float* rs = (float*)(lds + DF_AW + DF_SQ_WORDS);                     // [16 groups][32]
+  const int c = tid & 31, grp = tid >> 5;
+  const int per = (nW + DF_RG - 1) / DF_RG;
   uint32_t* err = a.bar + 64;
   bool bad = false;
   for (int rd = 0; rd < rounds; ++rd) {
-    const int task = rd * NU + uitem;
+    const int task = rd * NW + witem;
     const bool valid = task < tasks;
     const int m = valid ? task / np : 0, p = valid ? task - m * np : 0;
     const int w0 = grp * per, cnt = valid ? max(0, min(per, nW - w0)) : 0;
@@ -651,10 +652,10 @@ __device__ __forceinline__ bool df_reduce_phase(const DArgs& a, const uint32_t t
     __syncthreads();
     if (*sdead) return true;
     if (rd == 0) DF_STAMP(slot);
-    if (valid && ut < 32) {
+    if (valid && tid < 32) {
       float v = rs[c];
 #pragma unroll
-      for (int gq = 1; gq < 8; ++gq) v += rs[gq * 32 + c];
+      for (int gq = 1; gq < DF_RG; ++gq) v += rs[gq * 32 + c];
       v += __uint_as_float((uint32_t)hw);
       const size_t o = (size_t)m * d + 32 * p + c;
       st_wordf(h_out + o, v, tag);
@@ -1426,7 +1427,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   const bool g_q = has(u0, s_qkv, n_qkv, st) || has(u1, s_qkv, n_qkv, st) || st * n_qkv > NU,
              g_a = has(u0, s_att, n_att, st) || has(u1, s_att, n_att, st),
              g_o = has(u0, s_o, n_o, st) || has(u1, s_o, n_o, st), g_g = (int)blockIdx.x < a.g_mlp,
-             g_r = has(u0, s_red, n_red) || has(u1, s_red, n_red) || n_red > NU, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
+             g_r = df_item_of_unit((int)blockIdx.x, s_red >> 1, (int)gridDim.x) < n_red || n_red > (int)gridDim.x, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
 
   DF_STAMP(1);
   df_reserve_blocks(a, tag_v);
