@@ -1380,6 +1380,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
             n_att = a.n_seqs * a.nkv * (WHOLE ? 1 : a.n_parts) * ntile, n_o = np, n_gu = a.ffn >> 4,
             n_lg = (((a.vocab + 15) >> 4) + 1) >> 1;
   const int st = a.small_stride;
+  const int st_lg = 2 * n_lg <= NU ? 2 : 1;               // the head's items: a workgroup each where there are enough (a CU's intake bounds an item's weight stream)
   const int s_qkv = (2 * a.g_mlp) % NU, s_att = (s_qkv + st * n_qkv) % NU, s_o = (s_att + st * n_att) % NU,
             s_red = (s_o + st * n_o) % NU;
   auto make_qkv = [&](const DArgs& a, int l) {
@@ -1415,7 +1416,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   auto make_head = [&](const DArgs& a) {
     DPhase x = DPhase{};
     x.A = a.hg + (size_t)(2 * L) * a.st_h; x.sq = a.sq + (size_t)(2 * L) * a.st_sq;
-    x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.stride = 1; x.logits = a.logits;
+    x.W0 = a.head; x.W1 = a.head; x.N = a.vocab; x.K = a.d; x.gs = 1; x.items = n_lg; x.shift = 0; x.stride = st_lg; x.logits = a.logits;
     return x;
   };
   // which phase kinds this wave's unit / this workgroup has a round-0 item in
@@ -1427,7 +1428,7 @@ __global__ void __launch_bounds__(PBLOCK) k_forward_dataflow(DArgs) {
   const bool g_q = has(u0, s_qkv, n_qkv, st) || has(u1, s_qkv, n_qkv, st) || st * n_qkv > NU,
              g_a = has(u0, s_att, n_att, st) || has(u1, s_att, n_att, st),
              g_o = has(u0, s_o, n_o, st) || has(u1, s_o, n_o, st), g_g = (int)blockIdx.x < a.g_mlp,
-             g_r = df_item_of_unit((int)blockIdx.x, s_red >> 1, (int)gridDim.x) < n_red || n_red > (int)gridDim.x, g_l = has(u0, 0, n_lg) || has(u1, 0, n_lg) || n_lg > NU;
+             g_r = df_item_of_unit((int)blockIdx.x, s_red >> 1, (int)gridDim.x) < n_red || n_red > (int)gridDim.x, g_l = has(u0, 0, n_lg, st_lg) || has(u1, 0, n_lg, st_lg) || st_lg * n_lg > NU;
 
   DF_STAMP(1);
   df_reserve_blocks(a, tag_v);
