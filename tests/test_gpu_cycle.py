@@ -473,13 +473,14 @@ def test_captured_cycle_replays_like_the_eager_cycle(workload, K, cycles):
     torch.cuda.synchronize()
 
 
-def test_verify_of_512_rows_against_the_oracle():
-    """64 ragged sequences x (K+1 = 8) rows = 512 rows, the most one verification takes, on the small bf16 shape: every
+@pytest.mark.parametrize("B", [64, 128])
+def test_verify_of_many_sequences_against_the_oracle(B):
+    """64 or 128 ragged sequences x (K+1 = 8) rows = 512 or 1024 rows (the most one verification takes) on the small bf16 shape: every
     sequence's logits, probabilities and decision against the oracle, block tables and free stack against the allocator
     model, two steps (the second after 64 different commits)."""
     from tests.parity import Pair, verify_parity_step
     shape = si.model_shape("mini_bf16")
-    B, K, steps = 64, 7, 2
+    K, steps = 7, 2
     rng0 = np.random.default_rng(64)
     lens = [int(n) for n in rng0.integers(18, 140, size=B)]
     cap = max(lens) + steps * (K + 1) + 20
@@ -494,7 +495,7 @@ def test_verify_of_512_rows_against_the_oracle():
         assert pair.kv.last_forward_path() == 1
         worst = max(worst, max(r["dlogits"] for r in res))
         ns += [r["n"] for r in res]
-        for b in (0, 17, 63):
+        for b in (0, 17, B - 1):
             pair.check_state(b, 2e-2, layers=[shape["n_layers"] - 1])
         pair.check_free_stack()
     assert 0 < worst < 2e-2 and len(set(ns)) > 2
